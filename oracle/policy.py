@@ -1,0 +1,136 @@
+"""Oracle policy: commit rule, block advance, MergeSync.  TEST INFRASTRUCTURE ONLY.
+
+Written from Eq. 1 (Sec. 2.1), the merge and sync paragraphs of Sec. 4.1 and Alg. 1 / Alg. 2
+(App. D).  Where those leave a choice open the reading taken is noted next to the code.
+All of it is sequential, in-place Python over small arrays.
+"""
+from dataclasses import dataclass, field
+import numpy as np
+
+
+@dataclass
+class Branch:
+    """Branch state S_k of Alg. 1: index, block size, current window [start, end), done flag."""
+    k: int
+    b: int
+    start: int
+    end: int
+    done: bool = False
+    tokens_merged: int = 0
+    committed_threshold: int = 0
+    committed_fallback: int = 0
+    mean_conf: float = 0.0        # mean top-1 confidence over the rows of the latest decode
+    synced_from: int = -1         # leader index if the last MergeSync copied a row into this one
+
+
+def tokens_decoded(X, k, L_p, mask_id):
+    """Progress of branch k = number of generation positions that hold a token.
+    (Alg. 2 compares tokens_decoded and Alg. 1 returns argmax progress; both are read as
+    this count, which also equals the leader's count right after a sync copies its row.)"""
+    return int(np.count_nonzero(X[k, L_p:] != mask_id))
+
+
+def decode_current_block(X, br, rows, conf, pred, tau_dec, mask_id):
+    """Eq. 1 on branch br's window.  rows: positions that were masked when the forward ran
+    (ascending); conf/pred: their top-1 confidence and token.  A masked position commits its
+    argmax token if conf >= tau_dec or it is i*, the most confident masked position
+    (lowest position on ties); everything else keeps its value.  Returns committed positions."""
+    if len(rows) == 0:
+        return []
+    conf = np.asarray(conf, dtype=np.float64)
+    istar = int(np.argmax(conf))            # first maximum = lowest position
+    out = []
+    for j, i in enumerate(rows):
+        assert X[br.k, i] == mask_id
+        if conf[j] >= tau_dec or j == istar:
+            X[br.k, i] = pred[j]
+            out.append(int(i))
+            if conf[j] >= tau_dec:
+                br.committed_threshold += 1
+            else:
+                br.committed_fallback += 1
+    br.mean_conf = float(conf.mean())
+    return out
+
+
+def advance_block(X, br, L, mask_id):
+    """Slide the window forward over fully decoded blocks; done when it runs off the end."""
+    while not br.done and not np.any(X[br.k, br.start:br.end] == mask_id):
+        br.start = br.end
+        br.end = min(br.end + br.b, L)
+        if br.start >= L:
+            br.done = True
+            br.start = br.end = L
+
+
+def realign_window(X, br, L_p, L, mask_id):
+    """After a sync: move the window to the block (on the branch's own grid, which starts at
+    the end of the prompt) that contains the first masked position; no mask left -> done."""
+    masked = np.nonzero(X[br.k, L_p:] == mask_id)[0]
+    if len(masked) == 0:
+        br.done, br.start, br.end = True, L, L
+        return
+    f = L_p + int(masked[0])
+    br.start = L_p + ((f - L_p) // br.b) * br.b
+    br.end = min(br.start + br.b, L)
+    br.done = False
+
+
+def pick_leader(X, branches, L_p, mask_id, leader_rule):
+    """rule 0 (Alg. 2 line 1): most tokens decoded, ties -> higher mean confidence -> lower
+    index.  rule 1 (tiny workload): highest mean confidence, ties -> lower index."""
+    def key(br):
+        td = tokens_decoded(X, br.k, L_p, mask_id)
+        return (-td, -br.mean_conf, br.k) if leader_rule == 0 else (-br.mean_conf, br.k)
+    return min(branches, key=key)
+
+
+def compatible(X, s, d, mask_id):
+    """Sec. 4.1: every position decoded in both rows holds the same token."""
+    both = (X[s] != mask_id) & (X[d] != mask_id)
+    return bool(np.all(X[s][both] == X[d][both]))
+
+
+def merge_sync(X, branches, prob, L_p, L, mask_id, tau_merge, tau_sync, leader_rule, copy_row):
+    """Alg. 2.  prob(d, i, v) -> P_d(i, v), the destination's own probability of token v at
+    position i; copy_row(src, dst) copies cache row and probability map (sync).
+    Returns (merges [(d, i, v, s)], syncs [(d, leader)])."""
+    merges, syncs = [], []
+    for br in branches:
+        br.synced_from = -1
+    lead = pick_leader(X, branches, L_p, mask_id, leader_rule)
+    if tokens_decoded(X, lead.k, L_p, mask_id) == 0:
+        return merges, syncs
+    # active = not done; most advanced first, index breaks ties
+    order = sorted([br for br in branches if not br.done],
+                   key=lambda br: (-tokens_decoded(X, br.k, L_p, mask_id), br.k))
+    for d in order:
+        if d.done:                      # finished by an earlier step of this same pass
+            continue
+        srcs = [s for s in order if s is not d and compatible(X, s.k, d.k, mask_id)]
+        union = sorted({i for s in srcs for i in range(s.start, s.end)})
+        for i in union:
+            if X[d.k, i] != mask_id:
+                continue
+            cands = [s for s in srcs if X[s.k, i] != mask_id]
+            if not cands:
+                continue
+            ps = [prob(d.k, i, int(X[s.k, i])) for s in cands]
+            j = int(np.argmax(ps))      # first maximum = earliest source in the order
+            if ps[j] > tau_merge:
+                X[d.k, i] = X[cands[j].k, i]
+                d.tokens_merged += 1
+                merges.append((d.k, int(i), int(X[d.k, i]), cands[j].k))
+        advance_block(X, d, L, mask_id)
+    for d in branches:                  # hard sync, in index order
+        if d.done or d is lead:
+            continue
+        gap = tokens_decoded(X, lead.k, L_p, mask_id) - tokens_decoded(X, d.k, L_p, mask_id)
+        if gap > tau_sync:
+            X[d.k, :] = X[lead.k, :]
+            copy_row(lead.k, d.k)
+            d.mean_conf = lead.mean_conf
+            realign_window(X, d, L_p, L, mask_id)
+            d.synced_from = lead.k
+            syncs.append((d.k, lead.k))
+    return merges, syncs
