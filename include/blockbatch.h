@@ -1,0 +1,186 @@
+/*
+ * blockbatch.h - C ABI of the BlockBatch branch-batched denoising path for MI355X (gfx950).
+ *
+ * The calls follow Alg. 1 (App. D) of the paper.  One request = one prompt decoded by N
+ * block-size branches; each branch owns a token row X_k, a window [start, end) and a KV
+ * cache row (Sec. 5.1, App. D.1).
+ *
+ *   bb_refresh(BB_INIT)      InitialFullForward: one full forward on prompt + masks, the
+ *                            cache shared by every branch row, logits for all G positions
+ *   bb_denoise_step          GetActiveBranches + PackActiveBlocks + BatchedBlockForward
+ *                            (Sec. 4.2) + top-1 confidence / argmax per masked row (Sec. 2.1)
+ *   bb_merge_commit          DecodeCurrentBlock (Eq. 1), UpdateProbabilityMap,
+ *                            AdvanceCompletedBlocks, MergeSync (Alg. 2), refresh cadence
+ *   bb_refresh(BB_PERIODIC)  RefreshIfNeeded: K <- F(x) for every unfinished branch (App. A.1)
+ *
+ * Conventions
+ *   - Every call returns 0 (BB_OK) or a negative error code; bb_last_error() gives a text.
+ *     Nothing throws or aborts across this boundary.
+ *   - All device work is enqueued on the HIP stream given to bb_create and is asynchronous,
+ *     except where a call copies results to host memory (stated per call).
+ *   - The library allocates no device memory: the caller passes one workspace of at least
+ *     bb_workspace_bytes() bytes (256-byte aligned), which the context owns until bb_destroy.
+ *   - Pointers named *_host are host memory, *_dev device memory.  Device pointers handed
+ *     out in bb_step_view point into the workspace and stay valid until the next forward.
+ *   - Branch / request state lives on the device; the host never needs to read it inside
+ *     the decode loop.
+ */
+#ifndef BLOCKBATCH_H
+#define BLOCKBATCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BB_OK       0
+#define BB_EINVAL  -1   /* bad argument or unsupported shape */
+#define BB_ESTATE  -2   /* call order violated (e.g. step before the init refresh) */
+#define BB_ENOMEM  -3   /* workspace too small / limits exceeded */
+#define BB_EHIP    -4   /* HIP runtime error */
+
+#define BB_INIT      0
+#define BB_PERIODIC  1
+
+#define BB_MAX_BRANCHES 8
+
+typedef struct bb_ctx bb_ctx;
+
+/* Model shape.  Pre-norm transformer, bidirectional attention, rotate-half RoPE, RMSNorm,
+ * SwiGLU; head_dim must be 64 or 128; d_model, d_ffn multiples of 16; the row counts of all
+ * projections multiples of 32; vocab a multiple of 32.  mask_id is the [M] token (Sec. 2.1);
+ * its logit is treated as -inf so it is never predicted. */
+typedef struct {
+    int n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+    float rope_base, rms_eps;
+    int qkv_bias;
+    int mask_id;
+} bb_model_cfg;
+
+/* Decoding hyper-parameters (Alg. 1 "Require" line; App. E.3 values tau_sync 8, tau_merge 0.5). */
+typedef struct {
+    float tau_dec;          /* Eq. 1: commit if confidence >= tau_dec (or most confident)   */
+    float tau_merge;        /* Alg. 2: accept a merged token if P_d(i,v) >  tau_merge       */
+    int   tau_sync;         /* Alg. 2: copy the leader if its lead is      >  tau_sync      */
+    int   refresh_interval; /* R: block forwards between full-sequence refreshes            */
+    int   leader_rule;      /* 0: most tokens decoded (Alg. 2); 1: highest mean confidence  */
+} bb_decode_cfg;
+
+/* Capacity the workspace is sized for. */
+typedef struct {
+    int max_requests;       /* concurrently open requests                                   */
+    int max_branches;       /* branches per request, <= BB_MAX_BRANCHES                     */
+    int max_seq_len;        /* prompt + generation length                                   */
+    int max_gen_len;        /* generation length                                            */
+    int max_step_rows;      /* packed query rows of one bb_denoise_step (sum of block sizes
+                               over all requests in the call)                               */
+} bb_limits;
+
+/* One weight tensor, bf16, row-major [rows][cols] ([out][in] for projections; a norm gain or
+ * bias has rows = 1).  Names: tok_emb, lm_head, final_norm, and per layer i: l{i}.attn_norm,
+ * l{i}.wq, l{i}.wk, l{i}.wv, l{i}.bq, l{i}.bk, l{i}.bv (only with qkv_bias), l{i}.wo,
+ * l{i}.ffn_norm, l{i}.w_gate, l{i}.w_up, l{i}.w_down. */
+typedef struct {
+    const char* name;
+    const void* data;       /* host or device memory, see on_device; caller keeps ownership */
+    int on_device;
+    long rows, cols;
+} bb_tensor;
+
+/* Per-branch state S_k (Alg. 1 line 4) plus the counters Alg. 2 keeps. */
+typedef struct {
+    int block;              /* b_k                                                          */
+    int start, end;         /* current window, absolute positions                           */
+    int done;
+    int tokens_decoded;     /* generation positions holding a token (as of the last commit) */
+    int tokens_merged;      /* cumulative                                                   */
+    int committed_threshold, committed_fallback;   /* cumulative Eq. 1 commits by arm       */
+    int synced_from;        /* leader index if the last bb_merge_commit copied into this row, else -1 */
+    float mean_conf;        /* mean top-1 confidence over the rows of the latest decode     */
+} bb_branch_state;
+
+/* Device-side results of the latest forward (bb_denoise_step, or bb_refresh(BB_INIT) where
+ * the rows are the G generation positions of the common row).  counts_dev[0] = M_q packed
+ * query rows, counts_dev[1] = M_lm rows that received logits. */
+typedef struct {
+    const int*   counts_dev;
+    const int*   row_branch_dev;   /* [M_q] request_slot * max_branches + branch            */
+    const int*   row_pos_dev;      /* [M_q] absolute position                               */
+    const int*   lm_row_dev;       /* [M_lm] index into the packed rows                     */
+    const int*   argmax_dev;       /* [M_lm] top-1 token                                    */
+    const float* conf_dev;         /* [M_lm] top-1 probability                              */
+    const float* lse_dev;          /* [M_lm] log-sum-exp of the row's logits                */
+    const float* logits_dev;       /* [M_lm][vocab] fp32, mask column as computed (ignore)  */
+    int rows_capacity;
+} bb_step_view;
+
+/* Host-side summary of one request after bb_merge_commit. */
+typedef struct {
+    int n_branches;
+    int refresh_due;               /* R block forwards have run since the last refresh      */
+    int all_done;
+    int nfe_init, nfe_block, nfe_refresh;   /* one batched forward = one NFE (Sec. 5.1)      */
+    bb_branch_state branch[BB_MAX_BRANCHES];
+} bb_request_stats;
+
+size_t bb_workspace_bytes(const bb_model_cfg* model, const bb_limits* limits);
+
+/* Create a context on the current device.  workspace_dev: device memory, 256-byte aligned,
+ * >= bb_workspace_bytes(); hip_stream: a hipStream_t (NULL = default stream). */
+int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decode_cfg* decode,
+              const bb_limits* limits, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+int bb_destroy(bb_ctx* ctx);
+const char* bb_last_error(const bb_ctx* ctx);
+
+/* Copy the tensors into the workspace, re-tiled into MFMA fragment order (projections),
+ * widened to fp32 (gains, biases) or as they are (embedding).  May be called several times
+ * with disjoint subsets; synchronises the stream before returning so host sources can be
+ * released.  Every tensor must have been loaded before the first forward. */
+int bb_load_weights(bb_ctx* ctx, const bb_tensor* tensors, int n);
+
+/* Alg. 1 lines 1-4: X_k = prompt + G masks for each of the N branches, windows at the end of
+ * the prompt.  prompt_host: L_p token ids; block_sizes_host: N block sizes. */
+int bb_request_open(bb_ctx* ctx, const int32_t* prompt_host, int L_p, int G,
+                    const int* block_sizes_host, int N, int* req_id_out);
+int bb_request_close(bb_ctx* ctx, int req_id);
+
+/* Full-sequence forward(s).  BB_INIT: once per request, before anything else.  BB_PERIODIC:
+ * recompute the cache row of every unfinished branch from its current tokens. */
+int bb_refresh(bb_ctx* ctx, const int* req_ids_host, int n, int mode);
+
+/* One batched block forward over the current windows of all unfinished branches of the
+ * listed requests; view_out (may be NULL) receives device pointers to its results. */
+int bb_denoise_step(bb_ctx* ctx, const int* req_ids_host, int n, bb_step_view* view_out);
+
+/* Commit / merge / sync on the results of the latest forward of the listed requests.
+ * stats_out_host (may be NULL): n entries; when given, the call waits for the stream and
+ * copies the summaries to the host; when NULL the call is asynchronous. */
+int bb_merge_commit(bb_ctx* ctx, const int* req_ids_host, int n, bb_request_stats* stats_out_host);
+
+/* ---- inspection and teacher forcing (tests, harness); all synchronise the stream ---- */
+/* Device pointers to the results of the latest forward (what bb_denoise_step returns in
+ * view_out; after bb_refresh(BB_INIT) of one request the rows are its G generation positions). */
+int bb_get_view(bb_ctx* ctx, bb_step_view* view_out);
+int bb_get_tokens(bb_ctx* ctx, int req_id, int32_t* X_host /* [N][L] */);
+int bb_get_stats(bb_ctx* ctx, int req_id, bb_request_stats* out_host);
+/* Overwrite token rows and branch windows (block sizes, counters are kept). */
+int bb_set_state(bb_ctx* ctx, int req_id, const int32_t* X_host /* [N][L] */,
+                 const bb_branch_state* branches_host /* [N] */);
+/* Cache row of one branch in one layer as the attention of that branch sees it, widened to
+ * fp32: K_host, V_host [L][n_kv_heads][head_dim]. */
+int bb_get_kv(bb_ctx* ctx, int req_id, int branch, int layer, float* K_host, float* V_host);
+/* Plain device-to-host copy after a stream synchronise (for the pointers of bb_step_view). */
+int bb_read_device(bb_ctx* ctx, const void* src_dev, void* dst_host, size_t bytes);
+int bb_synchronize(bb_ctx* ctx);
+/* C[M][N] = A[M][K] . W[N][K]^T through the same packing, tiling and MFMA kernels the
+ * forward uses (kernel-level parity test).  A_host fp32, W_host bf16 bits, C_host fp32;
+ * split_k = 0 lets the library choose. */
+int bb_debug_gemm(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, float* C_host,
+                  int M, int N, int K, int split_k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

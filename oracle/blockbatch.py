@@ -119,10 +119,8 @@ class OracleRequest:
             self.V[dst][i][:] = self.V[src][i]
         self.P[dst] = self.P[src]
 
-    def commit_merge(self):
-        """DecodeCurrentBlock + UpdateProbabilityMap per branch, AdvanceCompletedBlocks,
-        MergeSync, and the refresh cadence (a refresh is due once R block forwards have run
-        since the last one).  Returns a dict of what happened."""
+    def decode_all(self):
+        """DecodeCurrentBlock (Eq. 1) + UpdateProbabilityMap for every branch that received logits."""
         r, p = self.pending, self.p
         commits = []
         probs = softmax_rows(r.logits) if len(r.pos) else np.zeros((0, self.m.s.vocab))
@@ -130,18 +128,29 @@ class OracleRequest:
             sel = np.nonzero(r.branch == br.k)[0]
             if len(sel) == 0 or br.done:
                 continue
-            msk = self.X[br.k, r.pos[sel]] == self.mask_id       # init rows may be unmasked? never, kept for safety
-            sel = sel[msk]
             commits += [(br.k, i) for i in decode_current_block(
                 self.X, br, r.pos[sel], r.conf[sel], r.pred[sel], p.tau_dec, self.mask_id)]
             self.P[br.k, r.pos[sel] - self.L_p] = probs[sel]
+        self.pending = None
+        return commits
+
+    def advance_all(self):
         for br in self.br:
             advance_block(self.X, br, self.L, self.mask_id)
-        merges, syncs = merge_sync(
-            self.X, self.br, lambda d, i, v: self.P[d, i - self.L_p, v], self.L_p, self.L, self.mask_id,
-            p.tau_merge, p.tau_sync, p.leader_rule, self._copy_row)
-        self.refresh_due = self.since_refresh >= p.refresh_interval and any(not b.done for b in self.br)
-        self.pending = None
+
+    def merge_sync_all(self, prob=None):
+        prob = prob or (lambda d, i, v: self.P[d, i - self.L_p, v])
+        return merge_sync(self.X, self.br, prob, self.L_p, self.L, self.mask_id,
+                          self.p.tau_merge, self.p.tau_sync, self.p.leader_rule, self._copy_row)
+
+    def commit_merge(self):
+        """DecodeCurrentBlock + UpdateProbabilityMap per branch, AdvanceCompletedBlocks,
+        MergeSync, and the refresh cadence (a refresh is due once R block forwards have run
+        since the last one).  Returns a dict of what happened."""
+        commits = self.decode_all()
+        self.advance_all()
+        merges, syncs = self.merge_sync_all()
+        self.refresh_due = self.since_refresh >= self.p.refresh_interval and any(not b.done for b in self.br)
         return {"commits": commits, "merges": merges, "syncs": syncs, "refresh_due": self.refresh_due}
 
     # ---- convenience ------------------------------------------------------------

@@ -1,0 +1,560 @@
+// Host side of libblockbatch: context, workspace layout, weight loading and the four calls
+// of the boundary.  The host only sequences kernel launches; every step of the path runs in
+// the kernels and all request state stays on the device.
+#include "bb_internal.h"
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+struct LayerW {
+    u32x4 *wqkv, *wo, *wgu, *wdown;     // tiled bf16
+    float *g_attn, *g_ffn, *bqkv;       // fp32
+};
+
+struct HostReq { int in_use, L_p, G, L, N, blocks[BB_MAX_BRANCHES], initialised; };
+
+struct bb_ctx {
+    bb_model_cfg m; bb_decode_cfg dc; bb_limits lim;
+    hipStream_t stream;
+    char* ws; size_t ws_bytes;
+    Dev D;
+    std::vector<LayerW> layers;
+    uint16_t* emb; u32x4* lm; float* g_final;
+    std::vector<char> loaded;           // per tensor slot
+    int n_expected;
+    // activations
+    float *h, *qkv, *part, *gu, *logits, *dbg;
+    u32x4* Apk; half_t* Q; char* stage;
+    size_t qkv_elems, part_elems, gu_elems, stage_bytes, dbg_bytes;
+    int refresh_rows_cap;
+    std::vector<HostReq> reqs;
+    char* d_stats;                      // device staging for stats copies
+    std::string err;
+    int last_forward_rows, last_lm_cap;
+};
+
+static int fail(bb_ctx* c, int code, const std::string& msg) { if (c) c->err = msg; return code; }
+#define HIPCHK(c, expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) \
+    return fail(c, BB_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_)); } while (0)
+
+// ---- workspace layout (one pass computes sizes, the same pass assigns pointers) -----------------
+struct Bump {
+    char* base; size_t off;
+    template <class T> T* take(size_t n) {
+        off = align_up(off, 256);
+        T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+        off += n * sizeof(T);
+        return p;
+    }
+};
+
+// Largest split-K output over every row count the forward may be called with.
+static size_t buf_elems(int rows_cap, int N, int K) {
+    size_t best = 0;
+    for (int rows = 32; rows <= (rows_cap + 31) / 32 * 32; rows += 32) {
+        GemmPlan p = gemm_plan(rows, N, K, 0);
+        size_t e = (size_t)p.split_k * rows * N;
+        if (e > best) best = e;
+    }
+    return best;
+}
+
+static int check_cfg(const bb_model_cfg* m, const bb_limits* l, std::string* why) {
+    auto bad = [&](const char* s) { if (why) *why = s; return BB_EINVAL; };
+    if (!m || !l) return bad("null config");
+    if (m->head_dim != 64 && m->head_dim != 128) return bad("head_dim must be 64 or 128");
+    if (m->n_q_heads % m->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
+    if (m->d_model % 16 || m->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
+    if (m->d_model % 32 || (2 * m->d_ffn) % 32 || m->vocab % 32) return bad("projection row counts must be multiples of 32");
+    if (m->mask_id < 0 || m->mask_id >= m->vocab) return bad("mask_id out of range");
+    if (l->max_branches < 1 || l->max_branches > BB_MAX_BRANCHES) return bad("max_branches out of range");
+    if (l->max_requests < 1 || l->max_requests * l->max_branches > 256) return bad("max_requests * max_branches must be <= 256");
+    if (l->max_gen_len < 1 || l->max_gen_len >= l->max_seq_len) return bad("max_gen_len must be in [1, max_seq_len)");
+    if (l->max_step_rows < 1) return bad("max_step_rows must be positive");
+    return BB_OK;
+}
+
+static void layout(bb_ctx* c, char* base, size_t* total) {
+    const bb_model_cfg& m = c->m; const bb_limits& l = c->lim;
+    Bump b{base, 0};
+    Dev& D = c->D;
+    const int lpad = (int)align_up(l.max_seq_len, BB_PAGE);
+    const int nqkv = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim, nq = m.n_q_heads * m.head_dim;
+    const int refresh_rows = l.max_branches * l.max_seq_len;
+    const int rows_cap = std::max(l.max_step_rows, refresh_rows);
+    const int rows_pad = (rows_cap + 31) / 32 * 32;
+    const int lm_cap = std::max(l.max_step_rows, l.max_gen_len);
+    const int lm_pad = (lm_cap + 31) / 32 * 32;
+    const int nbr = l.max_requests * l.max_branches;
+    const size_t phys_rows = (size_t)l.max_requests * (l.max_branches + 1);
+    D.n_layers = m.n_layers; D.d = m.d_model; D.hq = m.n_q_heads; D.hkv = m.n_kv_heads; D.hd = m.head_dim;
+    D.f = m.d_ffn; D.vocab = m.vocab; D.mask_id = m.mask_id; D.qkv_bias = m.qkv_bias; D.nqkv = nqkv;
+    D.rms_eps = m.rms_eps;
+    D.tau_dec = c->dc.tau_dec; D.tau_merge = c->dc.tau_merge; D.tau_sync = c->dc.tau_sync;
+    D.refresh_interval = c->dc.refresh_interval; D.leader_rule = c->dc.leader_rule;
+    D.max_req = l.max_requests; D.max_br = l.max_branches; D.lpad = lpad; D.n_pages = lpad / BB_PAGE;
+    D.gmax = l.max_gen_len; D.rows_cap = rows_cap; D.lm_cap = lm_cap; D.phys_per_req = l.max_branches + 1;
+    c->refresh_rows_cap = refresh_rows;
+    // state (zeroed at create)
+    D.hdr = b.take<ReqHeader>(l.max_requests);
+    D.br = b.take<bb_branch_state>(nbr);
+    D.X = b.take<int>((size_t)nbr * lpad);
+    D.table = b.take<int>((size_t)nbr * D.n_pages);
+    D.map_hf = b.take<float>((size_t)nbr * D.gmax * m.d_model);
+    D.map_lse = b.take<float>((size_t)nbr * D.gmax);
+    D.map_conf = b.take<float>((size_t)nbr * D.gmax);
+    D.map_pred = b.take<int>((size_t)nbr * D.gmax);
+    D.rope_cos = b.take<float>((size_t)lpad * m.head_dim / 2);
+    D.rope_sin = b.take<float>((size_t)lpad * m.head_dim / 2);
+    D.counts = b.take<int>(16);
+    D.row_tok = b.take<int>(rows_pad); D.row_pos = b.take<int>(rows_pad);
+    D.row_gbr = b.take<int>(rows_pad); D.row_phys = b.take<int>(rows_pad);
+    D.seg_off = b.take<int>(nbr); D.seg_rows = b.take<int>(nbr);
+    D.lm_row = b.take<int>(lm_pad);
+    D.out_pred = b.take<int>(lm_pad); D.out_conf = b.take<float>(lm_pad); D.out_lse = b.take<float>(lm_pad);
+    D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
+    D.req_list = b.take<int>(l.max_requests);
+    c->d_stats = b.take<char>(sizeof(ReqHeader) + sizeof(bb_branch_state) * BB_MAX_BRANCHES);
+    D.Kc = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim);
+    D.Vt = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim);
+    size_t state_end = align_up(b.off, 256);
+    // activations
+    const int kmax = std::max(std::max(m.d_model, m.d_ffn), nq);
+    c->h = b.take<float>((size_t)rows_pad * m.d_model);
+    c->Apk = b.take<u32x4>((size_t)rows_pad * kmax / 8 * BB_SPLIT);
+    c->Q = b.take<half_t>((size_t)rows_pad * nq);
+    c->qkv_elems = buf_elems(rows_cap, nqkv, m.d_model);
+    c->part_elems = std::max(buf_elems(rows_cap, m.d_model, nq), buf_elems(rows_cap, m.d_model, m.d_ffn));
+    c->gu_elems = buf_elems(rows_cap, 2 * m.d_ffn, m.d_model);
+    c->qkv = b.take<float>(c->qkv_elems);
+    c->part = b.take<float>(c->part_elems);
+    c->gu = b.take<float>(c->gu_elems);
+    c->logits = b.take<float>((size_t)lm_pad * m.vocab);
+    c->dbg_bytes = 2 * (size_t)lpad * m.n_kv_heads * m.head_dim * sizeof(float);
+    c->dbg = b.take<float>(c->dbg_bytes / sizeof(float));
+    size_t biggest = (size_t)m.vocab * m.d_model;
+    biggest = std::max(biggest, (size_t)m.d_ffn * m.d_model);
+    biggest = std::max(biggest, (size_t)nq * m.d_model);
+    c->stage_bytes = biggest * 2;
+    c->stage = b.take<char>(c->stage_bytes);
+    // weights
+    c->emb = b.take<uint16_t>((size_t)m.vocab * m.d_model);
+    c->lm = b.take<u32x4>((size_t)m.vocab * m.d_model / 8);
+    c->g_final = b.take<float>(m.d_model);
+    c->layers.resize(m.n_layers);
+    for (auto& L : c->layers) {
+        L.wqkv = b.take<u32x4>((size_t)nqkv * m.d_model / 8);
+        L.wo = b.take<u32x4>((size_t)m.d_model * nq / 8);
+        L.wgu = b.take<u32x4>((size_t)2 * m.d_ffn * m.d_model / 8);
+        L.wdown = b.take<u32x4>((size_t)m.d_model * m.d_ffn / 8);
+        L.g_attn = b.take<float>(m.d_model); L.g_ffn = b.take<float>(m.d_model);
+        L.bqkv = b.take<float>(nqkv);
+    }
+    (void)state_end;
+    *total = align_up(b.off, 256);
+}
+
+extern "C" size_t bb_workspace_bytes(const bb_model_cfg* model, const bb_limits* limits) {
+    if (check_cfg(model, limits, nullptr) != BB_OK) return 0;
+    bb_ctx tmp{};
+    tmp.m = *model; tmp.lim = *limits; tmp.dc = bb_decode_cfg{};
+    size_t total = 0;
+    layout(&tmp, nullptr, &total);
+    return total;
+}
+
+extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decode_cfg* decode,
+                         const bb_limits* limits, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    if (!out || !decode || !workspace_dev) return BB_EINVAL;
+    std::string why;
+    if (check_cfg(model, limits, &why) != BB_OK) return BB_EINVAL;
+    if (decode->refresh_interval < 1) return BB_EINVAL;
+    if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return BB_EINVAL;
+    bb_ctx* c = new bb_ctx{};
+    c->m = *model; c->dc = *decode; c->lim = *limits;
+    c->stream = (hipStream_t)hip_stream;
+    size_t total = 0;
+    layout(c, (char*)workspace_dev, &total);
+    if (total > workspace_bytes) { delete c; return BB_ENOMEM; }
+    c->ws = (char*)workspace_dev; c->ws_bytes = workspace_bytes;
+    c->reqs.assign(limits->max_requests, HostReq{});
+    c->n_expected = 3 + model->n_layers * (model->qkv_bias ? 12 : 9);
+    c->loaded.assign(3 + model->n_layers * 12, 0);
+    // zero state, caches and activations once (fp16 garbage in never-written cache tails would
+    // otherwise reach 0 * NaN in the attention's P.V product)
+    size_t zero_bytes = (char*)c->emb - c->ws;
+    hipError_t e = hipMemsetAsync(c->ws, 0, zero_bytes, c->stream);
+    if (e != hipSuccess) { delete c; return BB_EHIP; }
+    // rotary table in double precision on the host
+    const int half = model->head_dim / 2, lpad = c->D.lpad;
+    std::vector<float> cs((size_t)lpad * half), sn((size_t)lpad * half);
+    for (int p = 0; p < lpad; ++p)
+        for (int j = 0; j < half; ++j) {
+            double th = (double)p * std::pow((double)model->rope_base, -2.0 * j / model->head_dim);
+            cs[(size_t)p * half + j] = (float)std::cos(th);
+            sn[(size_t)p * half + j] = (float)std::sin(th);
+        }
+    e = hipMemcpyAsync(c->D.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(c->D.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) { delete c; return BB_EHIP; }
+    *out = c;
+    return BB_OK;
+}
+
+extern "C" int bb_destroy(bb_ctx* ctx) {
+    if (!ctx) return BB_EINVAL;
+    hipStreamSynchronize(ctx->stream);
+    delete ctx;
+    return BB_OK;
+}
+
+extern "C" const char* bb_last_error(const bb_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+// ---- weights ------------------------------------------------------------------------------------
+__global__ void widen_bf16_kernel(const uint16_t* __restrict__ src, float* __restrict__ dst, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = bf16_to_f32(src[i]);
+}
+
+static int load_one(bb_ctx* c, const bb_tensor& t) {
+    const bb_model_cfg& m = c->m;
+    const int hd = m.head_dim, nq = m.n_q_heads * hd, nkv = m.n_kv_heads * hd, d = m.d_model, f = m.d_ffn;
+    std::string name = t.name ? t.name : "";
+    size_t bytes = (size_t)t.rows * t.cols * 2;
+    if (!t.data || t.rows <= 0 || t.cols <= 0) return fail(c, BB_EINVAL, "bad tensor " + name);
+    if (bytes > c->stage_bytes) return fail(c, BB_EINVAL, "tensor larger than any expected: " + name);
+    const uint16_t* src = (const uint16_t*)t.data;
+    if (!t.on_device) {
+        HIPCHK(c, hipMemcpyAsync(c->stage, t.data, bytes, hipMemcpyHostToDevice, c->stream));
+        src = (const uint16_t*)c->stage;
+    }
+    auto expect = [&](long r, long k) { return t.rows == r && t.cols == k; };
+    auto widen = [&](float* dst, size_t n) {
+        widen_bf16_kernel<<<(unsigned)((n + 255) / 256), 256, 0, c->stream>>>(src, dst, n);
+    };
+    int slot = -1; bool ok = false;
+    if (name == "tok_emb") {
+        slot = 0; ok = expect(m.vocab, d);
+        if (ok) HIPCHK(c, hipMemcpyAsync(c->emb, src, bytes, hipMemcpyDeviceToDevice, c->stream));
+    } else if (name == "lm_head") {
+        slot = 1; ok = expect(m.vocab, d);
+        if (ok) launch_tile_weights(src, m.vocab, d, c->lm, 0, c->stream);
+    } else if (name == "final_norm") {
+        slot = 2; ok = t.rows * t.cols == d;
+        if (ok) widen(c->g_final, d);
+    } else if (name.size() > 2 && name[0] == 'l') {
+        size_t dot = name.find('.');
+        if (dot == std::string::npos) return fail(c, BB_EINVAL, "unknown tensor " + name);
+        int li = atoi(name.substr(1, dot - 1).c_str());
+        if (li < 0 || li >= m.n_layers) return fail(c, BB_EINVAL, "layer out of range: " + name);
+        LayerW& L = c->layers[li];
+        std::string k = name.substr(dot + 1);
+        const char* keys[12] = {"attn_norm", "wq", "wk", "wv", "bq", "bk", "bv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"};
+        int ki = -1;
+        for (int i = 0; i < 12; ++i) if (k == keys[i]) ki = i;
+        if (ki < 0) return fail(c, BB_EINVAL, "unknown tensor " + name);
+        slot = 3 + li * 12 + ki;
+        switch (ki) {
+            case 0: ok = t.rows * t.cols == d; if (ok) widen(L.g_attn, d); break;
+            case 1: ok = expect(nq, d); if (ok) launch_tile_weights(src, nq, d, L.wqkv, 0, c->stream); break;
+            case 2: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq, c->stream); break;
+            case 3: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq + nkv, c->stream); break;
+            case 4: ok = m.qkv_bias && t.rows * t.cols == nq; if (ok) widen(L.bqkv, nq); break;
+            case 5: ok = m.qkv_bias && t.rows * t.cols == nkv; if (ok) widen(L.bqkv + nq, nkv); break;
+            case 6: ok = m.qkv_bias && t.rows * t.cols == nkv; if (ok) widen(L.bqkv + nq + nkv, nkv); break;
+            case 7: ok = expect(d, nq); if (ok) launch_tile_weights(src, d, nq, L.wo, 0, c->stream); break;
+            case 8: ok = t.rows * t.cols == d; if (ok) widen(L.g_ffn, d); break;
+            case 9: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 0, c->stream); break;
+            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, f, c->stream); break;
+            case 11: ok = expect(d, f); if (ok) launch_tile_weights(src, d, f, L.wdown, 0, c->stream); break;
+        }
+    } else return fail(c, BB_EINVAL, "unknown tensor " + name);
+    if (!ok) return fail(c, BB_EINVAL, "shape mismatch for " + name);
+    HIPCHK(c, hipGetLastError());
+    if (!t.on_device) HIPCHK(c, hipStreamSynchronize(c->stream));      // staging is reused by the next tensor
+    c->loaded[slot] = 1;
+    return BB_OK;
+}
+
+extern "C" int bb_load_weights(bb_ctx* ctx, const bb_tensor* tensors, int n) {
+    if (!ctx || !tensors || n < 0) return BB_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        int rc = load_one(ctx, tensors[i]);
+        if (rc != BB_OK) return rc;
+    }
+    HIPCHK(ctx, hipStreamSynchronize(ctx->stream));
+    return BB_OK;
+}
+
+static bool weights_complete(const bb_ctx* c) {
+    int n = 0;
+    for (char x : c->loaded) n += x;
+    return n == c->n_expected;
+}
+
+// ---- requests ---------------------------------------------------------------------------------------
+extern "C" int bb_request_open(bb_ctx* c, const int32_t* prompt, int L_p, int G, const int* blocks, int N, int* req_id) {
+    if (!c || !prompt || !blocks || !req_id) return BB_EINVAL;
+    if (L_p < 1 || G < 1 || N < 1) return fail(c, BB_EINVAL, "bad request shape");
+    if (N > c->lim.max_branches || L_p + G > c->lim.max_seq_len || G > c->lim.max_gen_len)
+        return fail(c, BB_ENOMEM, "request exceeds the limits the workspace was sized for");
+    int slot = -1;
+    for (int i = 0; i < c->lim.max_requests; ++i) if (!c->reqs[i].in_use) { slot = i; break; }
+    if (slot < 0) return fail(c, BB_ENOMEM, "no free request slot");
+    const int L = L_p + G, lpad = c->D.lpad, mb = c->D.max_br;
+    std::vector<int> X((size_t)mb * lpad, c->m.mask_id);
+    std::vector<bb_branch_state> br(mb);
+    memset(br.data(), 0, sizeof(bb_branch_state) * mb);
+    for (int k = 0; k < N; ++k) {
+        if (blocks[k] < 1) return fail(c, BB_EINVAL, "block size must be positive");
+        for (int i = 0; i < L_p; ++i) {
+            if (prompt[i] < 0 || prompt[i] >= c->m.vocab || prompt[i] == c->m.mask_id)
+                return fail(c, BB_EINVAL, "prompt token out of range or equal to the mask id");
+            X[(size_t)k * lpad + i] = prompt[i];
+        }
+        br[k].block = blocks[k]; br[k].start = L_p; br[k].end = std::min(L_p + blocks[k], L); br[k].synced_from = -1;
+    }
+    ReqHeader H; memset(&H, 0, sizeof(H));
+    H.in_use = 1; H.L_p = L_p; H.G = G; H.L = L; H.N = N;
+    HIPCHK(c, hipMemcpyAsync(c->D.X + (size_t)slot * mb * lpad, X.data(), X.size() * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->D.br + slot * mb, br.data(), sizeof(bb_branch_state) * mb, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(c->D.hdr + slot, &H, sizeof(H), hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HostReq& R = c->reqs[slot];
+    R = HostReq{}; R.in_use = 1; R.L_p = L_p; R.G = G; R.L = L; R.N = N;
+    for (int k = 0; k < N; ++k) R.blocks[k] = blocks[k];
+    *req_id = slot;
+    return BB_OK;
+}
+
+extern "C" int bb_request_close(bb_ctx* c, int req_id) {
+    if (!c || req_id < 0 || req_id >= c->lim.max_requests || !c->reqs[req_id].in_use) return BB_EINVAL;
+    HIPCHK(c, hipMemsetAsync(c->D.hdr + req_id, 0, sizeof(ReqHeader), c->stream));
+    c->reqs[req_id].in_use = 0;
+    return BB_OK;
+}
+
+static int check_reqs(bb_ctx* c, const int* ids, int n, bool need_init) {
+    if (!c || !ids || n < 1 || n > c->lim.max_requests) return BB_EINVAL;
+    for (int i = 0; i < n; ++i) {
+        if (ids[i] < 0 || ids[i] >= c->lim.max_requests || !c->reqs[ids[i]].in_use) return fail(c, BB_EINVAL, "unknown request id");
+        for (int j = 0; j < i; ++j) if (ids[j] == ids[i]) return fail(c, BB_EINVAL, "request listed twice");
+        if (need_init && !c->reqs[ids[i]].initialised) return fail(c, BB_ESTATE, "request has not had its initial refresh");
+    }
+    if (!weights_complete(c)) return fail(c, BB_ESTATE, "weights not fully loaded");
+    return BB_OK;
+}
+
+// ---- the forward -----------------------------------------------------------------------------------
+// mode 0: block step with LM head; 1: initial full forward with LM head over lm_cap rows
+// (results broadcast to all branches); 2: cache-only refresh (stops after the last K,V write).
+static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, int n_segs, int max_seg_rows) {
+    const bb_model_cfg& m = c->m; const Dev& D = c->D; hipStream_t s = c->stream;
+    const int d = m.d_model, nq = m.n_q_heads * m.head_dim, f = m.d_ffn, nqkv = D.nqkv;
+    const int mt = (rows_cap + 31) / 32, rows_pad = mt * 32;
+    launch_embed(D, c->emb, c->h, rows_cap, s);
+    GemmPlan p_down{1, 0};
+    for (int li = 0; li < m.n_layers; ++li) {
+        const LayerW& W = c->layers[li];
+        const size_t pstride = (size_t)rows_pad * d;
+        launch_rmsnorm_pack(D, c->h, c->part, li ? p_down.split_k : 0, pstride, W.g_attn, c->Apk, rows_cap, mt, 0, 0, s);
+        GemmPlan p = gemm_plan(rows_cap, nqkv, d, 0);
+        launch_gemm(W.wqkv, c->Apk, c->qkv, mt, nqkv, d, p, nqkv, (size_t)rows_pad * nqkv, s);
+        launch_rope_kv(D, c->qkv, p.split_k, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s);
+        if (mode == 2 && li == m.n_layers - 1) break;
+        launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, s);
+        p = gemm_plan(rows_cap, d, nq, 0);
+        launch_gemm(W.wo, c->Apk, c->part, mt, d, nq, p, d, pstride, s);
+        launch_rmsnorm_pack(D, c->h, c->part, p.split_k, pstride, W.g_ffn, c->Apk, rows_cap, mt, 0, 0, s);
+        p = gemm_plan(rows_cap, 2 * f, d, 0);
+        launch_gemm(W.wgu, c->Apk, c->gu, mt, 2 * f, d, p, 2 * f, (size_t)rows_pad * 2 * f, s);
+        launch_swiglu_pack(D, c->gu, p.split_k, (size_t)rows_pad * 2 * f, c->Apk, rows_cap, mt, s);
+        p_down = gemm_plan(rows_cap, d, f, 0);
+        launch_gemm(W.wdown, c->Apk, c->part, mt, d, f, p_down, d, pstride, s);
+    }
+    if (mode != 2) {
+        const int mt_lm = (lm_cap + 31) / 32;
+        launch_rmsnorm_pack(D, c->h, c->part, p_down.split_k, (size_t)rows_pad * d, c->g_final, c->Apk, lm_cap, mt_lm, 1, mode == 1, s);
+        GemmPlan p = gemm_plan(lm_cap, m.vocab, d, 1);
+        launch_gemm(c->lm, c->Apk, c->logits, mt_lm, m.vocab, d, p, m.vocab, 0, s);
+        launch_vocab_reduce(D, c->logits, lm_cap, mode == 1, s);
+    }
+    c->last_forward_rows = rows_cap; c->last_lm_cap = lm_cap;
+    HIPCHK(c, hipGetLastError());
+    return BB_OK;
+}
+
+static int upload_req_list(bb_ctx* c, const int* ids, int n) {
+    HIPCHK(c, hipMemcpyAsync(c->D.req_list, ids, sizeof(int) * n, hipMemcpyHostToDevice, c->stream));
+    return BB_OK;
+}
+
+extern "C" int bb_refresh(bb_ctx* c, const int* ids, int n, int mode) {
+    int rc = check_reqs(c, ids, n, mode == BB_PERIODIC);
+    if (rc != BB_OK) return rc;
+    if (mode != BB_INIT && mode != BB_PERIODIC) return fail(c, BB_EINVAL, "bad refresh mode");
+    for (int i = 0; i < n; ++i) {
+        HostReq& R = c->reqs[ids[i]];
+        if (mode == BB_INIT && R.initialised) return fail(c, BB_ESTATE, "request already initialised");
+        const int slot = ids[i];
+        launch_pack_refresh(c->D, slot, mode, c->stream);
+        if (mode == BB_INIT) rc = forward(c, R.L, R.G, 1, slot * c->D.max_br, 1, R.L);
+        else rc = forward(c, R.N * R.L, 0, 2, slot * c->D.max_br, R.N, R.L);
+        if (rc != BB_OK) return rc;
+        if (mode == BB_INIT) R.initialised = 1;
+    }
+    return BB_OK;
+}
+
+static void fill_view(bb_ctx* c, bb_step_view* v) {
+    const Dev& D = c->D;
+    v->counts_dev = D.counts; v->row_branch_dev = D.row_gbr; v->row_pos_dev = D.row_pos; v->lm_row_dev = D.lm_row;
+    v->argmax_dev = D.out_pred; v->conf_dev = D.out_conf; v->lse_dev = D.out_lse; v->logits_dev = c->logits;
+    v->rows_capacity = D.lm_cap;
+}
+
+extern "C" int bb_denoise_step(bb_ctx* c, const int* ids, int n, bb_step_view* view) {
+    int rc = check_reqs(c, ids, n, true);
+    if (rc != BB_OK) return rc;
+    int rows = 0, maxb = 0;
+    for (int i = 0; i < n; ++i) {
+        const HostReq& R = c->reqs[ids[i]];
+        for (int k = 0; k < R.N; ++k) { rows += std::min(R.blocks[k], R.G); maxb = std::max(maxb, std::min(R.blocks[k], R.G)); }
+    }
+    if (rows > c->lim.max_step_rows) return fail(c, BB_ENOMEM, "step rows exceed max_step_rows");
+    if ((rc = upload_req_list(c, ids, n)) != BB_OK) return rc;
+    launch_pack_step(c->D, n, c->stream);
+    launch_page_copies(c->D, c->stream);
+    rc = forward(c, rows, rows, 0, 0, c->D.max_req * c->D.max_br, maxb);
+    if (rc == BB_OK && view) fill_view(c, view);
+    return rc;
+}
+
+static int read_stats(bb_ctx* c, int slot, bb_request_stats* out) {
+    ReqHeader H; bb_branch_state br[BB_MAX_BRANCHES];
+    HIPCHK(c, hipMemcpy(&H, c->D.hdr + slot, sizeof(H), hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(br, c->D.br + slot * c->D.max_br, sizeof(bb_branch_state) * c->D.max_br, hipMemcpyDeviceToHost));
+    memset(out, 0, sizeof(*out));
+    out->n_branches = H.N; out->refresh_due = H.refresh_due; out->all_done = H.all_done;
+    out->nfe_init = H.nfe_init; out->nfe_block = H.nfe_block; out->nfe_refresh = H.nfe_refresh;
+    for (int k = 0; k < H.N; ++k) out->branch[k] = br[k];
+    return BB_OK;
+}
+
+extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stats* stats) {
+    int rc = check_reqs(c, ids, n, true);
+    if (rc != BB_OK) return rc;
+    if ((rc = upload_req_list(c, ids, n)) != BB_OK) return rc;
+    launch_commit_merge(c->D, n, reinterpret_cast<const uint16_t*>(c->lm), c->stream);
+    HIPCHK(c, hipGetLastError());
+    if (stats) {
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        for (int i = 0; i < n; ++i) if ((rc = read_stats(c, ids[i], &stats[i])) != BB_OK) return rc;
+    }
+    return BB_OK;
+}
+
+// ---- inspection and teacher forcing ---------------------------------------------------------------------
+static int check_one(bb_ctx* c, int id) {
+    if (!c || id < 0 || id >= c->lim.max_requests || !c->reqs[id].in_use) return BB_EINVAL;
+    return BB_OK;
+}
+
+extern "C" int bb_synchronize(bb_ctx* c) {
+    if (!c) return BB_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return BB_OK;
+}
+
+extern "C" int bb_read_device(bb_ctx* c, const void* src, void* dst, size_t bytes) {
+    if (!c || !src || !dst) return BB_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost));
+    return BB_OK;
+}
+
+extern "C" int bb_get_view(bb_ctx* c, bb_step_view* view) {
+    if (!c || !view) return BB_EINVAL;
+    fill_view(c, view);
+    return BB_OK;
+}
+
+extern "C" int bb_get_tokens(bb_ctx* c, int id, int32_t* X) {
+    if (check_one(c, id) != BB_OK || !X) return BB_EINVAL;
+    const HostReq& R = c->reqs[id];
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    for (int k = 0; k < R.N; ++k)
+        HIPCHK(c, hipMemcpy(X + (size_t)k * R.L, c->D.X + ((size_t)id * c->D.max_br + k) * c->D.lpad, R.L * 4, hipMemcpyDeviceToHost));
+    return BB_OK;
+}
+
+extern "C" int bb_get_stats(bb_ctx* c, int id, bb_request_stats* out) {
+    if (check_one(c, id) != BB_OK || !out) return BB_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return read_stats(c, id, out);
+}
+
+extern "C" int bb_set_state(bb_ctx* c, int id, const int32_t* X, const bb_branch_state* brs) {
+    if (check_one(c, id) != BB_OK || !X || !brs) return BB_EINVAL;
+    const HostReq& R = c->reqs[id];
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    bb_branch_state cur[BB_MAX_BRANCHES];
+    HIPCHK(c, hipMemcpy(cur, c->D.br + id * c->D.max_br, sizeof(bb_branch_state) * c->D.max_br, hipMemcpyDeviceToHost));
+    for (int k = 0; k < R.N; ++k) {
+        if (brs[k].start < R.L_p || brs[k].end > R.L || brs[k].start > brs[k].end) return fail(c, BB_EINVAL, "window out of range");
+        for (int i = 0; i < R.L; ++i)
+            if (X[(size_t)k * R.L + i] < 0 || X[(size_t)k * R.L + i] >= c->m.vocab) return fail(c, BB_EINVAL, "token out of range");
+        HIPCHK(c, hipMemcpy(c->D.X + ((size_t)id * c->D.max_br + k) * c->D.lpad, X + (size_t)k * R.L, R.L * 4, hipMemcpyHostToDevice));
+        cur[k].start = brs[k].start; cur[k].end = brs[k].end; cur[k].done = brs[k].done;
+        cur[k].mean_conf = brs[k].mean_conf;
+    }
+    HIPCHK(c, hipMemcpy(c->D.br + id * c->D.max_br, cur, sizeof(bb_branch_state) * c->D.max_br, hipMemcpyHostToDevice));
+    return BB_OK;
+}
+
+extern "C" int bb_get_kv(bb_ctx* c, int id, int branch, int layer, float* K, float* V) {
+    if (check_one(c, id) != BB_OK || !K || !V) return BB_EINVAL;
+    const HostReq& R = c->reqs[id];
+    if (branch < 0 || branch >= R.N || layer < 0 || layer >= c->m.n_layers) return BB_EINVAL;
+    const size_t n = (size_t)R.L * c->m.n_kv_heads * c->m.head_dim;
+    float* dK = c->dbg; float* dV = c->dbg + n;
+    launch_read_kv(c->D, id, branch, layer, dK, dV, R.L, c->stream);
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(K, dK, n * 4, hipMemcpyDeviceToHost));
+    HIPCHK(c, hipMemcpy(V, dV, n * 4, hipMemcpyDeviceToHost));
+    return BB_OK;
+}
+
+extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
+    if (!c || !A || !W || !C || M < 1 || N < 32 || K < 16 || N % 32 || K % 16 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
+    const int mt = (M + 31) / 32, rows_pad = mt * 32;
+    GemmPlan p = gemm_plan(M, N, K, split_k);
+    // carve private buffers out of the activation region [h, emb): nothing else runs meanwhile
+    Bump b{(char*)c->h, 0};
+    float* dA = b.take<float>((size_t)M * K);
+    uint16_t* dW = b.take<uint16_t>((size_t)N * K);
+    u32x4* dWt = b.take<u32x4>((size_t)N * K / 8);
+    u32x4* dAp = b.take<u32x4>((size_t)rows_pad * K / 8 * BB_SPLIT);
+    const size_t c_elems = (size_t)p.split_k * rows_pad * N;
+    float* dC = b.take<float>(c_elems);
+    if (b.off > (size_t)((char*)c->emb - (char*)c->h)) return fail(c, BB_ENOMEM, "debug gemm does not fit the activation region");
+    HIPCHK(c, hipMemcpyAsync(dA, A, (size_t)M * K * 4, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemcpyAsync(dW, W, (size_t)N * K * 2, hipMemcpyHostToDevice, c->stream));
+    launch_tile_weights(dW, N, K, dWt, 0, c->stream);
+    launch_pack_rows(dA, M, K, dAp, mt, c->stream);
+    launch_gemm(dWt, dAp, dC, mt, N, K, p, N, (size_t)rows_pad * N, c->stream);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    std::vector<float> tmp(c_elems);
+    HIPCHK(c, hipMemcpy(tmp.data(), dC, c_elems * 4, hipMemcpyDeviceToHost));
+    for (int mrow = 0; mrow < M; ++mrow)
+        for (int ncol = 0; ncol < N; ++ncol) {
+            float acc = 0.f;
+            for (int s = 0; s < p.split_k; ++s) acc += tmp[((size_t)s * rows_pad + mrow) * N + ncol];
+            C[(size_t)mrow * N + ncol] = acc;
+        }
+    return BB_OK;
+}

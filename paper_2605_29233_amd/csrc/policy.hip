@@ -1,0 +1,421 @@
+// Device-side scheduling and policy kernels: packing the active windows into one row list
+// (GetActiveBranches / PackActiveBlocks of Alg. 1), copy-on-write of cache pages, and the
+// commit / merge / sync step (Eq. 1 and Alg. 2) on the results of the latest forward.
+// All branch and request state lives in device memory, so a decode loop never has to read
+// anything back.
+#include "bb_internal.h"
+
+// ---- small workgroup reductions (blockDim.x == 256) ----------------------------------------
+static __device__ __forceinline__ int wg_sum_i(int v, int* sh) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return sh[0] + sh[1] + sh[2] + sh[3];
+}
+static __device__ __forceinline__ int wg_min_i(int v, int* sh) {
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return min(min(sh[0], sh[1]), min(sh[2], sh[3]));
+}
+static __device__ __forceinline__ float wg_sum_f(float v, float* sh) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// ---- packing --------------------------------------------------------------------------------
+// Block step: every unfinished branch of the listed requests contributes the rows of its
+// window; rows still masked are additionally listed for the LM head.  Pages under a window
+// that the branch does not own yet are queued for copy-on-write and re-pointed.
+__global__ __launch_bounds__(256) void pack_step_kernel(Dev D, int n_req) {
+    __shared__ int s_rows[256], s_lm[256], s_off[257], s_lmoff[257];
+    const int nb_all = D.max_req * D.max_br, nb = n_req * D.max_br, t = threadIdx.x;
+    for (int i = t; i < nb_all; i += 256) D.seg_rows[i] = 0;
+    if (t == 0) D.counts[2] = 0;
+    __syncthreads();
+    int slot = 0, k = 0, rows = 0, nlm = 0, start = 0, end = 0;
+    const int* Xr = nullptr;
+    if (t < nb) {
+        slot = D.req_list[t / D.max_br]; k = t % D.max_br;
+        const ReqHeader& H = D.hdr[slot];
+        const bb_branch_state& B = D.br[slot * D.max_br + k];
+        if (k < H.N && !B.done) {
+            start = B.start; end = B.end; rows = end - start;
+            Xr = D.X + ((size_t)slot * D.max_br + k) * D.lpad;
+            for (int i = start; i < end; ++i) nlm += Xr[i] == D.mask_id;
+        }
+        D.hdr[slot].pending[k] = rows > 0;
+    }
+    s_rows[t] = rows; s_lm[t] = nlm;
+    __syncthreads();
+    if (t == 0) {
+        int a = 0, b = 0;
+        for (int i = 0; i < nb; ++i) { s_off[i] = a; s_lmoff[i] = b; a += s_rows[i]; b += s_lm[i]; }
+        D.counts[0] = a; D.counts[1] = b;
+    }
+    __syncthreads();
+    if (t < nb && rows > 0) {
+        const int gbr = slot * D.max_br + k, own = slot * D.phys_per_req + k;
+        D.seg_off[gbr] = s_off[t]; D.seg_rows[gbr] = rows;
+        int c = s_lmoff[t];
+        for (int i = start; i < end; ++i) {
+            const int r = s_off[t] + (i - start);
+            D.row_tok[r] = Xr[i]; D.row_pos[r] = i; D.row_gbr[r] = gbr; D.row_phys[r] = own;
+            if (Xr[i] == D.mask_id) D.lm_row[c++] = r;
+        }
+        for (int p = start / BB_PAGE; p <= (end - 1) / BB_PAGE; ++p) {
+            int* e = &D.table[(size_t)gbr * D.n_pages + p];
+            if (*e != own) {
+                const int idx = atomicAdd(&D.counts[2], 1);
+                D.copies[idx] = PageCopy{*e, own, p, 0};
+                *e = own;
+            }
+        }
+    }
+    if (t < n_req) {
+        ReqHeader& H = D.hdr[D.req_list[t]];
+        H.since_refresh += 1; H.nfe_block += 1;
+    }
+}
+
+void launch_pack_step(const Dev& D, int n_req, hipStream_t s) { pack_step_kernel<<<1, 256, 0, s>>>(D, n_req); }
+
+// Full-sequence forward of one request.  mode BB_INIT: the common row (all branches are still
+// identical), written to the request's shared physical row that every branch's page table
+// then points to; logits for the G generation positions.  mode BB_PERIODIC: all L rows of
+// every unfinished branch, each into its own physical row.
+__global__ __launch_bounds__(256) void pack_refresh_kernel(Dev D, int slot, int mode) {
+    __shared__ int s_off[BB_MAX_BRANCHES + 1];
+    const int nb_all = D.max_req * D.max_br, t = threadIdx.x;
+    ReqHeader& H = D.hdr[slot];
+    const int L = H.L, N = H.N;
+    for (int i = t; i < nb_all; i += 256) D.seg_rows[i] = 0;
+    __syncthreads();
+    if (mode == BB_INIT) {
+        const int gbr = slot * D.max_br, shared_row = slot * D.phys_per_req + D.max_br;
+        const int* Xr = D.X + (size_t)gbr * D.lpad;
+        for (int i = t; i < L; i += 256) {
+            D.row_tok[i] = Xr[i]; D.row_pos[i] = i; D.row_gbr[i] = gbr; D.row_phys[i] = shared_row;
+        }
+        for (int j = t; j < H.G; j += 256) D.lm_row[j] = H.L_p + j;
+        for (int i = t; i < N * D.n_pages; i += 256)
+            D.table[(size_t)(gbr + i / D.n_pages) * D.n_pages + i % D.n_pages] = shared_row;
+        if (t == 0) {
+            D.seg_off[gbr] = 0; D.seg_rows[gbr] = L;
+            D.counts[0] = L; D.counts[1] = H.G; D.counts[2] = 0;
+            H.nfe_init += 1; H.since_refresh = 0; H.refresh_due = 0; H.initialised = 1;
+            for (int k = 0; k < BB_MAX_BRANCHES; ++k) H.pending[k] = k < N;
+        }
+        return;
+    }
+    if (t == 0) {
+        int a = 0;
+        for (int k = 0; k < N; ++k) { s_off[k] = a; if (!D.br[slot * D.max_br + k].done) a += L; }
+        s_off[N] = a;
+        D.counts[0] = a; D.counts[1] = 0; D.counts[2] = 0;
+        H.nfe_refresh += 1; H.since_refresh = 0; H.refresh_due = 0;
+    }
+    __syncthreads();
+    for (int k = 0; k < N; ++k) {
+        if (s_off[k + 1] == s_off[k]) continue;
+        const int gbr = slot * D.max_br + k, own = slot * D.phys_per_req + k;
+        const int* Xr = D.X + (size_t)gbr * D.lpad;
+        for (int i = t; i < L; i += 256) {
+            const int r = s_off[k] + i;
+            D.row_tok[r] = Xr[i]; D.row_pos[r] = i; D.row_gbr[r] = gbr; D.row_phys[r] = own;
+        }
+        for (int p = t; p < D.n_pages; p += 256) D.table[(size_t)gbr * D.n_pages + p] = own;
+        if (t == 0) { D.seg_off[gbr] = s_off[k]; D.seg_rows[gbr] = L; }
+    }
+}
+
+void launch_pack_refresh(const Dev& D, int slot, int mode, hipStream_t s) {
+    pack_refresh_kernel<<<1, 256, 0, s>>>(D, slot, mode);
+}
+
+// ---- page copies (copy-on-write before a block step, row copies after a sync) ------------------
+// Work item = (list entry, layer, eighth of the page); a fixed grid strides over the items.
+__global__ __launch_bounds__(256) void page_copy_kernel(Dev D) {
+    const int n = D.counts[2];
+    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
+    const int items = n * D.n_layers * 8;
+    const int krow = D.hkv * D.hd;                  // halfs per token in K; rows of V^T
+    for (int it = blockIdx.x; it < items; it += gridDim.x) {
+        const int e = it / (D.n_layers * 8), layer = (it / 8) % D.n_layers, part = it % 8;
+        const PageCopy pc = D.copies[e];
+        const int t0 = pc.page * BB_PAGE;
+        // K: 8 tokens of the page, contiguous
+        const size_t ks = ((((size_t)layer * phys_rows + pc.src) * D.lpad + t0 + part * 8) * krow);
+        const size_t kd = ((((size_t)layer * phys_rows + pc.dst) * D.lpad + t0 + part * 8) * krow);
+        const u32x4* s4 = reinterpret_cast<const u32x4*>(D.Kc + ks);
+        u32x4* d4 = reinterpret_cast<u32x4*>(D.Kc + kd);
+        for (int i = threadIdx.x; i < krow; i += 256) d4[i] = s4[i];          // 8 tokens * krow halfs / 8 per u32x4
+        // V^T: an eighth of the (head, dim) rows, 64 tokens (128 bytes) each
+        const int r0 = part * (krow / 8), r1 = (part + 1) * (krow / 8);
+        for (int i = threadIdx.x; i < (r1 - r0) * 8; i += 256) {
+            const int r = r0 + i / 8, q = i % 8;
+            const size_t vs = (((size_t)layer * phys_rows + pc.src) * krow + r) * D.lpad + t0 + q * 8;
+            const size_t vd = (((size_t)layer * phys_rows + pc.dst) * krow + r) * D.lpad + t0 + q * 8;
+            *reinterpret_cast<u32x4*>(D.Vt + vd) = *reinterpret_cast<const u32x4*>(D.Vt + vs);
+        }
+    }
+}
+
+void launch_page_copies(const Dev& D, hipStream_t s) { page_copy_kernel<<<1024, 256, 0, s>>>(D); }
+
+__global__ void zero_copy_count_kernel(Dev D) { D.counts[2] = 0; }
+
+// ---- commit / merge / sync ----------------------------------------------------------------------
+struct CommitShared {
+    int si[4]; float sf[4];
+    int decoded[BB_MAX_BRANCHES], order[BB_MAX_BRANCHES], compat[BB_MAX_BRANCHES];
+    int n_order, lead, istar, merged, thr, fb, go;
+};
+
+static __device__ int count_decoded(const Dev& D, const int* Xr, int L_p, int L, int* sh) {
+    int c = 0;
+    for (int i = L_p + threadIdx.x; i < L; i += 256) c += Xr[i] != D.mask_id;
+    return wg_sum_i(c, sh);
+}
+
+// AdvanceBlock: slide the window over blocks that hold no mask; past the end -> done.
+static __device__ void advance(const Dev& D, bb_branch_state* B, const int* Xr, int L, int* sh) {
+    while (true) {
+        __syncthreads();
+        if (B->done) break;
+        const int start = B->start, end = B->end;
+        int c = 0;
+        for (int i = start + threadIdx.x; i < end; i += 256) c += Xr[i] == D.mask_id;
+        c = wg_sum_i(c, sh);
+        if (c > 0) break;
+        if (threadIdx.x == 0) {
+            B->start = end; B->end = min(end + B->block, L);
+            if (B->start >= L) { B->done = 1; B->start = B->end = L; }
+        }
+    }
+    __syncthreads();
+}
+
+// P_d(i, v) = exp(hf . W_v - lse) with the hidden vector the destination stored for position i;
+// one wave, lanes stride over the model dimension.  W is the LM head in tiled fragment order.
+static __device__ float prob_of(const Dev& D, const u32x4* lm, const float* hf, float lse, int v) {
+    const int lane = threadIdx.x & 63, k8s = D.d >> 3;
+    float acc = 0.f;
+    for (int k8 = lane; k8 < k8s; k8 += 64) {
+        const u32x4 w = lm[tileW_u4(v, k8, k8s >> 1)];
+        const uint16_t* wb = reinterpret_cast<const uint16_t*>(&w);
+        const float* x = hf + k8 * 8;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) acc += x[q] * bf16_to_f32(wb[q]);
+    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    return expf(acc - lse);
+}
+
+__global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* __restrict__ lm) {
+    __shared__ CommitShared S;
+    const int slot = D.req_list[blockIdx.x], t = threadIdx.x;
+    ReqHeader& H = D.hdr[slot];
+    const int N = H.N, L_p = H.L_p, L = H.L, mask = D.mask_id;
+    bb_branch_state* B = D.br + slot * D.max_br;
+    int* X = D.X + (size_t)slot * D.max_br * D.lpad;
+    const size_t map0 = (size_t)slot * D.max_br * D.gmax;
+
+    // -- DecodeCurrentBlock (Eq. 1) for every branch that received logits ---------------------
+    for (int k = 0; k < N; ++k) {
+        __syncthreads();
+        if (!H.pending[k] || B[k].done) continue;
+        int* Xr = X + (size_t)k * D.lpad;
+        const int start = B[k].start, end = B[k].end;
+        const float* conf = D.map_conf + map0 + (size_t)k * D.gmax - L_p;
+        const int* pred = D.map_pred + map0 + (size_t)k * D.gmax - L_p;
+        // most confident masked position, lowest position on ties
+        float bc = -1.f; int bi = 0x7fffffff, nm = 0; float sc = 0.f;
+        for (int i = start + t; i < end; i += 256)
+            if (Xr[i] == mask) { ++nm; sc += conf[i]; if (conf[i] > bc) { bc = conf[i]; bi = i; } }
+        for (int o = 32; o > 0; o >>= 1) {
+            const float oc = __shfl_xor(bc, o, 64); const int oi = __shfl_xor(bi, o, 64);
+            if (oc > bc || (oc == bc && oi < bi)) { bc = oc; bi = oi; }
+        }
+        __shared__ float w_c[4]; __shared__ int w_i[4];
+        if ((t & 63) == 0) { w_c[t >> 6] = bc; w_i[t >> 6] = bi; }
+        nm = wg_sum_i(nm, S.si);
+        sc = wg_sum_f(sc, S.sf);
+        if (t == 0) {
+            float c = w_c[0]; int ii = w_i[0];
+            for (int w = 1; w < 4; ++w) if (w_c[w] > c || (w_c[w] == c && w_i[w] < ii)) { c = w_c[w]; ii = w_i[w]; }
+            S.istar = ii; S.thr = 0; S.fb = 0;
+        }
+        __syncthreads();
+        if (nm == 0) continue;
+        for (int i = start + t; i < end; i += 256)
+            if (Xr[i] == mask) {
+                const bool thr = conf[i] >= D.tau_dec;
+                if (thr || i == S.istar) { Xr[i] = pred[i]; atomicAdd(thr ? &S.thr : &S.fb, 1); }
+            }
+        __syncthreads();
+        if (t == 0) {
+            B[k].committed_threshold += S.thr; B[k].committed_fallback += S.fb;
+            B[k].mean_conf = sc / (float)nm;
+        }
+    }
+    __syncthreads();
+    if (t < BB_MAX_BRANCHES) H.pending[t] = 0;
+    // -- AdvanceCompletedBlocks ----------------------------------------------------------------
+    for (int k = 0; k < N; ++k) advance(D, &B[k], X + (size_t)k * D.lpad, L, S.si);
+    // -- MergeSync (Alg. 2) ---------------------------------------------------------------------
+    for (int k = 0; k < N; ++k) {
+        const int c = count_decoded(D, X + (size_t)k * D.lpad, L_p, L, S.si);
+        if (t == 0) { S.decoded[k] = c; B[k].synced_from = -1; }
+    }
+    __syncthreads();
+    if (t == 0) {
+        int lead = 0;
+        for (int k = 1; k < N; ++k) {
+            bool better;
+            if (D.leader_rule == 0)
+                better = S.decoded[k] > S.decoded[lead] ||
+                         (S.decoded[k] == S.decoded[lead] && B[k].mean_conf > B[lead].mean_conf);
+            else
+                better = B[k].mean_conf > B[lead].mean_conf;
+            if (better) lead = k;
+        }
+        S.lead = lead;
+        S.go = S.decoded[lead] > 0;
+        // active branches, most decoded first, index breaks ties (stable insertion sort)
+        int n = 0;
+        for (int k = 0; k < N; ++k) if (!B[k].done) {
+            int p = n++;
+            while (p > 0 && S.decoded[S.order[p - 1]] < S.decoded[k]) { S.order[p] = S.order[p - 1]; --p; }
+            S.order[p] = k;
+        }
+        S.n_order = n;
+    }
+    __syncthreads();
+    if (S.go) {
+        const int lead = S.lead, n_order = S.n_order;
+        for (int oi = 0; oi < n_order; ++oi) {
+            const int d = S.order[oi];
+            __syncthreads();
+            if (B[d].done) continue;
+            int* Xd = X + (size_t)d * D.lpad;
+            // CompatibleSources, evaluated once for this destination
+            int lo = L, hi = 0;
+            for (int oj = 0; oj < n_order; ++oj) {
+                const int s = S.order[oj];
+                if (s == d) { if (t == 0) S.compat[s] = 0; continue; }
+                const int* Xs = X + (size_t)s * D.lpad;
+                int bad = 0;
+                for (int i = t; i < L; i += 256) bad += Xs[i] != mask && Xd[i] != mask && Xs[i] != Xd[i];
+                bad = wg_sum_i(bad, S.si);
+                if (t == 0) S.compat[s] = bad == 0;
+                if (bad == 0) { lo = min(lo, B[s].start); hi = max(hi, B[s].end); }
+            }
+            if (t == 0) S.merged = 0;
+            __syncthreads();
+            // positions of the union of the sources' windows, one wave per position
+            for (int i = lo + (t >> 6); i < hi; i += 4) {
+                if (Xd[i] != mask) continue;
+                float best_p = -1.f; int best_v = -1;
+                const size_t mi = map0 + (size_t)d * D.gmax + (i - L_p);
+                for (int oj = 0; oj < n_order; ++oj) {
+                    const int s = S.order[oj];
+                    if (s == d || !S.compat[s] || i < B[s].start || i >= B[s].end) continue;   // in the union at all?
+                    best_v = -2; break;
+                }
+                if (best_v != -2) continue;
+                best_v = -1;
+                for (int oj = 0; oj < n_order; ++oj) {
+                    const int s = S.order[oj];
+                    if (s == d || !S.compat[s]) continue;
+                    const int v = X[(size_t)s * D.lpad + i];
+                    if (v == mask) continue;
+                    const float p = prob_of(D, lm, D.map_hf + mi * D.d, D.map_lse[mi], v);
+                    if (p > best_p) { best_p = p; best_v = v; }      // strict: earliest source keeps a tie
+                }
+                if (best_v >= 0 && best_p > D.tau_merge && (t & 63) == 0) { Xd[i] = best_v; atomicAdd(&S.merged, 1); }
+            }
+            __syncthreads();
+            if (t == 0) B[d].tokens_merged += S.merged;
+            advance(D, &B[d], Xd, L, S.si);
+            const int c = count_decoded(D, Xd, L_p, L, S.si);
+            if (t == 0) S.decoded[d] = c;
+            __syncthreads();
+        }
+        // hard synchronisation: copy the leader into branches that lag by more than tau_sync
+        for (int d = 0; d < N; ++d) {
+            __syncthreads();
+            if (B[d].done || d == lead || S.decoded[lead] - S.decoded[d] <= D.tau_sync) continue;
+            int* Xd = X + (size_t)d * D.lpad; const int* Xl = X + (size_t)lead * D.lpad;
+            for (int i = t; i < L; i += 256) Xd[i] = Xl[i];
+            const size_t md = map0 + (size_t)d * D.gmax, ml = map0 + (size_t)lead * D.gmax;
+            for (int j = t; j < H.G; j += 256) {
+                D.map_lse[md + j] = D.map_lse[ml + j]; D.map_conf[md + j] = D.map_conf[ml + j];
+                D.map_pred[md + j] = D.map_pred[ml + j];
+            }
+            const float4* hs = reinterpret_cast<const float4*>(D.map_hf + ml * D.d);
+            float4* hdst = reinterpret_cast<float4*>(D.map_hf + md * D.d);
+            for (size_t j = t; j < (size_t)H.G * D.d / 4; j += 256) hdst[j] = hs[j];
+            const int gd = slot * D.max_br + d, gl = slot * D.max_br + lead;
+            const int own = slot * D.phys_per_req + d, shared_row = slot * D.phys_per_req + D.max_br;
+            for (int p = t; p < (L + BB_PAGE - 1) / BB_PAGE; p += 256) {
+                const int src = D.table[(size_t)gl * D.n_pages + p];
+                if (src == shared_row) D.table[(size_t)gd * D.n_pages + p] = shared_row;
+                else {
+                    D.table[(size_t)gd * D.n_pages + p] = own;
+                    D.copies[atomicAdd(&D.counts[2], 1)] = PageCopy{src, own, p, 0};
+                }
+            }
+            __syncthreads();
+            // RealignBlockWindow: block of the branch's own grid that holds the first mask
+            int f = 0x7fffffff;
+            for (int i = L_p + t; i < L; i += 256) if (Xd[i] == mask) f = min(f, i);
+            f = wg_min_i(f, S.si);
+            if (t == 0) {
+                B[d].mean_conf = B[lead].mean_conf; B[d].synced_from = lead;
+                if (f == 0x7fffffff) { B[d].done = 1; B[d].start = B[d].end = L; }
+                else {
+                    B[d].start = L_p + (f - L_p) / B[d].block * B[d].block;
+                    B[d].end = min(B[d].start + B[d].block, L);
+                    B[d].done = 0;
+                }
+                S.decoded[d] = S.decoded[lead];
+            }
+        }
+    }
+    __syncthreads();
+    if (t == 0) {
+        int all = 1;
+        for (int k = 0; k < N; ++k) { B[k].tokens_decoded = S.decoded[k]; all &= B[k].done; }
+        H.all_done = all;
+        H.refresh_due = H.since_refresh >= D.refresh_interval && !all;
+    }
+}
+
+void launch_commit_merge(const Dev& D, int n_req, const uint16_t* lm_head, hipStream_t s) {
+    zero_copy_count_kernel<<<1, 1, 0, s>>>(D);
+    commit_merge_kernel<<<n_req, 256, 0, s>>>(D, reinterpret_cast<const u32x4*>(lm_head));
+    page_copy_kernel<<<1024, 256, 0, s>>>(D);
+}
+
+// ---- inspection -------------------------------------------------------------------------------
+__global__ void read_kv_kernel(Dev D, int gbr, int layer, float* __restrict__ K, float* __restrict__ V, int L) {
+    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
+    const int krow = D.hkv * D.hd;
+    const size_t n = (size_t)L * krow;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const int pos = (int)(i / krow), e = (int)(i % krow);
+        const int phys = D.table[(size_t)gbr * D.n_pages + pos / BB_PAGE];
+        K[i] = (float)D.Kc[(((size_t)layer * phys_rows + phys) * D.lpad + pos) * krow + e];
+        V[i] = (float)D.Vt[(((size_t)layer * phys_rows + phys) * krow + e) * D.lpad + pos];
+    }
+}
+
+void launch_read_kv(const Dev& D, int slot, int branch, int layer, float* K, float* V, int L, hipStream_t s) {
+    read_kv_kernel<<<1024, 256, 0, s>>>(D, slot * D.max_br + branch, layer, K, V, L);
+}

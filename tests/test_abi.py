@@ -1,0 +1,77 @@
+"""Host-only checks of the C-ABI library: it loads, exports every declared symbol, and its
+pure-host entry points behave (no GPU needed, no kernels run)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from workload import workload, WORKLOAD_NAMES
+from paper_2605_29233_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.lib_path()):
+        from paper_2605_29233_amd.build import build
+        build()
+    return binding.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    hdr = open(os.path.join(ROOT, "include", "blockbatch.h")).read()
+    declared = set(re.findall(r"\b(bb_[a-z_]+)\s*\(", hdr))
+    assert {"bb_load_weights", "bb_refresh", "bb_denoise_step", "bb_merge_commit"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} is declared in blockbatch.h but not exported"
+    assert set(binding.EXPORTS) == declared
+
+
+def _cfg(w):
+    m = w.model
+    mc = binding.bb_model_cfg(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn, m.vocab,
+                              m.rope_base, m.rms_eps, int(m.qkv_bias), m.mask_id)
+    L = max(w.prompt_lens) + w.gen_len
+    lim = binding.bb_limits(w.n_requests, len(w.block_sizes), L, w.gen_len, w.n_requests * sum(w.block_sizes))
+    return mc, lim
+
+
+@pytest.mark.parametrize("name", WORKLOAD_NAMES)
+def test_workspace_bytes_covers_weights_and_cache(lib, name):
+    w = workload(name)
+    mc, lim = _cfg(w)
+    n = lib.bb_workspace_bytes(C.byref(mc), C.byref(lim))
+    m = w.model
+    per_layer = ((m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim * m.d_model + m.d_model * m.n_q_heads * m.head_dim
+                 + 3 * m.d_ffn * m.d_model)
+    weights = 2 * (m.n_layers * per_layer + 2 * m.vocab * m.d_model)
+    kv = 2 * 2 * m.n_layers * w.n_requests * (len(w.block_sizes) + 1) * (max(w.prompt_lens) + w.gen_len) * m.n_kv_heads * m.head_dim
+    assert n >= weights + kv
+    assert n < 230 * 2 ** 30, "must fit one MI355X (288 GB) with room to spare"
+
+
+def test_struct_sizes_match_header_layout():
+    assert C.sizeof(binding.bb_model_cfg) == 11 * 4
+    assert C.sizeof(binding.bb_decode_cfg) == 5 * 4
+    assert C.sizeof(binding.bb_limits) == 5 * 4
+    assert C.sizeof(binding.BranchState) == 10 * 4
+    assert C.sizeof(binding.RequestStats) == 6 * 4 + 8 * 40
+
+
+def test_bad_shapes_are_rejected(lib):
+    w = workload("tiny")
+    mc, lim = _cfg(w)
+    mc.head_dim = 80
+    assert lib.bb_workspace_bytes(C.byref(mc), C.byref(lim)) == 0
+    mc, lim = _cfg(w)
+    lim.max_branches = 9
+    assert lib.bb_workspace_bytes(C.byref(mc), C.byref(lim)) == 0
+    mc, lim = _cfg(w)
+    mc.mask_id = mc.vocab
+    assert lib.bb_workspace_bytes(C.byref(mc), C.byref(lim)) == 0
+    ctx = C.c_void_p()
+    assert lib.bb_create(C.byref(ctx), C.byref(mc), None, C.byref(lim), None, 0, None) == -1
+    assert lib.bb_destroy(None) == -1
+    assert lib.bb_last_error(None) == b"null context"
