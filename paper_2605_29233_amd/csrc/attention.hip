@@ -8,6 +8,9 @@
 // and the partial results are combined through LDS in a fixed order, so the result does not
 // depend on scheduling.
 //
+// Q, K, V and the probabilities P each enter as two fp16 terms (hi + lo); every product keeps
+// the three leading cross terms (hi.hi + lo.hi + hi.lo), i.e. ~22 bits per operand.
+//
 // MFMA use (fp16 inputs, fp32 accumulate, 16x16x32):
 //   S^T[key][query]  = K[key][:] . Q[query][:]      A = K rows (as stored), B = Q rows
 //   O^T[d][query]   += V^T[d][key] . P^T[key][query] A = V^T (cache is stored transposed),
@@ -42,16 +45,18 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     const float scale = 1.0f / sqrtf((float)HD);
 
     // Q fragments (B operand): lane (query c, k group g) holds 8 consecutive head dims.
-    u32x4 qf[2][KS];
+    u32x4 qf[2][2][KS];                 // [query tile][term][k-step]
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         const int f = tile_base + 16 * qt + c;
         const bool ok = f < nflat;
         const int hig = ok ? f / seg_rows : 0, r = ok ? f % seg_rows : 0;
-        const half_t* qp = Q + ((size_t)(seg_off + r) * D.hq + kvh * group + hig) * HD + 8 * g;
+        const half_t* qp = Q + ((size_t)(seg_off + r) * D.hq + kvh * group + hig) * 2 * HD + 8 * g;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            qf[qt][ks] = ok ? *reinterpret_cast<const u32x4*>(qp + 32 * ks) : u32x4{0u, 0u, 0u, 0u};
+        for (int term = 0; term < 2; ++term)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                qf[qt][term][ks] = ok ? *reinterpret_cast<const u32x4*>(qp + term * HD + 32 * ks) : u32x4{0u, 0u, 0u, 0u};
     }
     float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
     f32x4 o[DT][2];
@@ -63,22 +68,27 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     for (int page = wave; page < n_pages; page += 4) {
         const int phys = D.table[(size_t)gbr * D.n_pages + page];
         const int t0 = page * BB_PAGE;
-        const half_t* Kb = D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + t0) * D.hkv + kvh) * HD;
-        const half_t* Vb = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + kvh) * HD * (size_t)D.lpad + t0;
+        const half_t* Kb = D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + t0) * D.hkv + kvh) * 2 * HD;
+        const half_t* Vb = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + kvh) * 2 * HD * (size_t)D.lpad + t0;
         f32x4 s[4][2];
 #pragma unroll
         for (int kt = 0; kt < 4; ++kt) {
             s[kt][0] = f32x4{0.f, 0.f, 0.f, 0.f}; s[kt][1] = s[kt][0];
-            const half_t* kp = Kb + (size_t)(16 * kt + c) * D.hkv * HD + 8 * g;
+            const half_t* kp = Kb + (size_t)(16 * kt + c) * D.hkv * 2 * HD + 8 * g;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const f16x8 kf = as_f16x8(*reinterpret_cast<const u32x4*>(kp + 32 * ks));
-                s[kt][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, as_f16x8(qf[0][ks]), s[kt][0], 0, 0, 0);
-                s[kt][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kf, as_f16x8(qf[1][ks]), s[kt][1], 0, 0, 0);
+                const f16x8 kh = as_f16x8(*reinterpret_cast<const u32x4*>(kp + 32 * ks));
+                const f16x8 kl = as_f16x8(*reinterpret_cast<const u32x4*>(kp + HD + 32 * ks));
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt) {
+                    s[kt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kl, as_f16x8(qf[qt][0][ks]), s[kt][qt], 0, 0, 0);
+                    s[kt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, as_f16x8(qf[qt][1][ks]), s[kt][qt], 0, 0, 0);
+                    s[kt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kh, as_f16x8(qf[qt][0][ks]), s[kt][qt], 0, 0, 0);
+                }
             }
         }
         // register r of s[kt][qt]: key t0 + 16 kt + 4 g + r, query 16 qt + c
-        f16x8 pf[2][2];
+        f16x8 pf[2][2], pl[2][2];           // probabilities, hi and lo terms
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt) {
             float mx = -INFINITY;
@@ -102,7 +112,9 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
                 for (int r = 0; r < 4; ++r) {
                     const float p = expf(s[kt][qt][r] - m_new);
                     sum += p;
-                    pf[kt >> 1][qt][(kt & 1) * 4 + r] = (_Float16)p;
+                    const _Float16 ph = (_Float16)p;
+                    pf[kt >> 1][qt][(kt & 1) * 4 + r] = ph;
+                    pl[kt >> 1][qt][(kt & 1) * 4 + r] = (_Float16)(p - (float)ph);
                 }
             l_run[qt] = l_run[qt] * alpha + sum;
             m_run[qt] = m_new;
@@ -113,15 +125,22 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             const half_t* vp = Vb + (size_t)(16 * dt + c) * D.lpad + 4 * g;
+            const half_t* vq = vp + (size_t)HD * D.lpad;        // lo term
 #pragma unroll
             for (int kk = 0; kk < 2; ++kk) {
-                f16x8 vf;
-                const f16x4 v0 = *reinterpret_cast<const f16x4*>(vp + 32 * kk);
-                const f16x4 v1 = *reinterpret_cast<const f16x4*>(vp + 32 * kk + 16);
+                f16x8 vh, vl;
+                const f16x4 h0 = *reinterpret_cast<const f16x4*>(vp + 32 * kk);
+                const f16x4 h1 = *reinterpret_cast<const f16x4*>(vp + 32 * kk + 16);
+                const f16x4 l0 = *reinterpret_cast<const f16x4*>(vq + 32 * kk);
+                const f16x4 l1 = *reinterpret_cast<const f16x4*>(vq + 32 * kk + 16);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) { vf[j] = v0[j]; vf[4 + j] = v1[j]; }
-                o[dt][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf[kk][0], o[dt][0], 0, 0, 0);
-                o[dt][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vf, pf[kk][1], o[dt][1], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) { vh[j] = h0[j]; vh[4 + j] = h1[j]; vl[j] = l0[j]; vl[4 + j] = l1[j]; }
+#pragma unroll
+                for (int qt = 0; qt < 2; ++qt) {
+                    o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vl, pf[kk][qt], o[dt][qt], 0, 0, 0);
+                    o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pl[kk][qt], o[dt][qt], 0, 0, 0);
+                    o[dt][qt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(vh, pf[kk][qt], o[dt][qt], 0, 0, 0);
+                }
             }
         }
     }

@@ -117,14 +117,14 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
     D.req_list = b.take<int>(l.max_requests);
     c->d_stats = b.take<char>(sizeof(ReqHeader) + sizeof(bb_branch_state) * BB_MAX_BRANCHES);
-    D.Kc = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim);
-    D.Vt = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim);
+    D.Kc = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
+    D.Vt = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
     size_t state_end = align_up(b.off, 256);
     // activations
     const int kmax = std::max(std::max(m.d_model, m.d_ffn), nq);
     c->h = b.take<float>((size_t)rows_pad * m.d_model);
     c->Apk = b.take<u32x4>((size_t)rows_pad * kmax / 8 * BB_SPLIT);
-    c->Q = b.take<half_t>((size_t)rows_pad * nq);
+    c->Q = b.take<half_t>((size_t)rows_pad * nq * 2);
     c->qkv_elems = buf_elems(rows_cap, nqkv, m.d_model);
     c->part_elems = std::max(buf_elems(rows_cap, m.d_model, nq), buf_elems(rows_cap, m.d_model, m.d_ffn));
     c->gu_elems = buf_elems(rows_cap, 2 * m.d_ffn, m.d_model);

@@ -40,8 +40,10 @@ struct Dev {
     bb_branch_state* br;        // [max_req][max_br]
     int* X;                     // [max_req][max_br][lpad]
     int* table;                 // [max_req][max_br][n_pages] -> physical cache row
-    half_t* Kc;                 // [n_layers][phys_rows][lpad][hkv][hd]
-    half_t* Vt;                 // [n_layers][phys_rows][hkv][hd][lpad]
+    // K,V are cached as two fp16 terms (hi + lo, ~22 significant bits): one fp16 term alone
+    // moves the logits of a 32-layer model by more than the parity tolerance.
+    half_t* Kc;                 // [n_layers][phys_rows][lpad][hkv][term][hd]
+    half_t* Vt;                 // [n_layers][phys_rows][hkv][term][hd][lpad]   (transposed)
     float* map_hf;              // [max_req][max_br][gmax][d]  final-norm hidden of the latest forward
     float* map_lse;             // [max_req][max_br][gmax]
     float* map_conf;            // [max_req][max_br][gmax]

@@ -106,8 +106,9 @@ void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_par
 }
 
 // q,k,v = sum of split-K partials (+ bias); rotate q and k by the row's absolute position
-// (pairs (j, j + hd/2), angle pos * base^(-2j/hd), from a host-computed table); write q as
-// fp16 for the attention kernel, k into the row's cache page and v into the transposed cache.
+// (pairs (j, j + hd/2), angle pos * base^(-2j/hd), from a host-computed table); write q for
+// the attention kernel, k into the row's cache page and v into the transposed cache, each as
+// two fp16 terms hi + lo.
 __global__ __launch_bounds__(256) void rope_kv_kernel(Dev D, const float* __restrict__ qkv, int n_partial,
                                                       size_t partial_stride, const float* __restrict__ bias,
                                                       half_t* __restrict__ Q, int layer) {
@@ -124,6 +125,11 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(Dev D, const float* __rest
         return v;
     };
     const int nq = D.hq * half, nk = D.hkv * half;
+    auto put = [](half_t* hi_p, half_t* lo_p, float y) {
+        const half_t hi = (half_t)y;
+        *hi_p = hi;
+        *lo_p = (half_t)(y - (float)hi);
+    };
     for (int idx = threadIdx.x; idx < nq + nk; idx += blockDim.x) {
         const bool isq = idx < nq;
         const int e = isq ? idx : idx - nq;
@@ -131,15 +137,17 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(Dev D, const float* __rest
         const int c0 = (isq ? 0 : D.hq * hd) + head * hd + j;
         const float x1 = val(c0), x2 = val(c0 + half), c = cs[j], s = sn[j];
         const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
-        half_t* dst = isq ? Q + ((size_t)row * D.hq + head) * hd
-                          : D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + pos) * D.hkv + head) * hd;
-        dst[j] = (half_t)y1;
-        dst[j + half] = (half_t)y2;
+        // both layouts: [.. head][term][hd]
+        half_t* dst = isq ? Q + ((size_t)row * D.hq + head) * 2 * hd
+                          : D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + pos) * D.hkv + head) * 2 * hd;
+        put(dst + j, dst + hd + j, y1);
+        put(dst + j + half, dst + hd + j + half, y2);
     }
     const int voff = (D.hq + D.hkv) * hd;
     for (int e = threadIdx.x; e < D.hkv * hd; e += blockDim.x) {
         const int head = e / hd, dd = e % hd;
-        D.Vt[((((size_t)layer * phys_rows + phys) * D.hkv + head) * hd + dd) * D.lpad + pos] = (half_t)val(voff + e);
+        half_t* base = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + head) * 2 * hd * (size_t)D.lpad;
+        put(base + (size_t)dd * D.lpad + pos, base + (size_t)(hd + dd) * D.lpad + pos, val(voff + e));
     }
 }
 

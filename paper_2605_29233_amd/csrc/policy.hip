@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void page_copy_kernel(Dev D) {
     const int n = D.counts[2];
     const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
     const int items = n * D.n_layers * 8;
-    const int krow = D.hkv * D.hd;                  // halfs per token in K; rows of V^T
+    const int krow = 2 * D.hkv * D.hd;              // halfs per token in K (two terms); rows of V^T
     for (int it = blockIdx.x; it < items; it += gridDim.x) {
         const int e = it / (D.n_layers * 8), layer = (it / 8) % D.n_layers, part = it % 8;
         const PageCopy pc = D.copies[e];
@@ -406,13 +406,15 @@ void launch_commit_merge(const Dev& D, int n_req, const uint16_t* lm_head, hipSt
 // ---- inspection -------------------------------------------------------------------------------
 __global__ void read_kv_kernel(Dev D, int gbr, int layer, float* __restrict__ K, float* __restrict__ V, int L) {
     const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
-    const int krow = D.hkv * D.hd;
+    const int krow = D.hkv * D.hd, hd = D.hd;
     const size_t n = (size_t)L * krow;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        const int pos = (int)(i / krow), e = (int)(i % krow);
+        const int pos = (int)(i / krow), e = (int)(i % krow), head = e / hd, dd = e % hd;
         const int phys = D.table[(size_t)gbr * D.n_pages + pos / BB_PAGE];
-        K[i] = (float)D.Kc[(((size_t)layer * phys_rows + phys) * D.lpad + pos) * krow + e];
-        V[i] = (float)D.Vt[(((size_t)layer * phys_rows + phys) * krow + e) * D.lpad + pos];
+        const half_t* kp = D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + pos) * D.hkv + head) * 2 * hd;
+        const half_t* vp = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + head) * 2 * hd * (size_t)D.lpad;
+        K[i] = (float)kp[dd] + (float)kp[hd + dd];
+        V[i] = (float)vp[(size_t)dd * D.lpad + pos] + (float)vp[(size_t)(hd + dd) * D.lpad + pos];
     }
 }
 

@@ -46,12 +46,16 @@ class SideBySide:
         self.diverged = False
 
     # -- forwards -----------------------------------------------------------------------------
-    def _compare_forward(self, ref, view):
+    def _compare_forward(self, ref, view, sel=None):
+        """sel: indices of this request's rows among the view's lm rows (None = all)."""
         rep = self.rep
-        assert view.m_lm == len(ref.pos), (view.m_lm, len(ref.pos))
-        if view.m_lm == 0:
+        n_mine = view.m_lm if sel is None else len(sel)
+        assert n_mine == len(ref.pos), (n_mine, len(ref.pos))
+        self._argmax_fragile = False
+        if n_mine == 0:
             return
-        lg = view.logits()
+        take = (lambda a: a) if sel is None else (lambda a: a[sel])
+        lg = take(view.logits())
         keep = np.arange(lg.shape[1]) != self.o.mask_id
         err = np.abs(lg[:, keep] - ref.logits[:, keep]).max()
         rep.max_logit_err = max(rep.max_logit_err, float(err))
@@ -61,9 +65,9 @@ class SideBySide:
         margin = srt[:, -1] - srt[:, -2]
         clear = margin > GUARD
         rep.argmax_in_band += int((~clear).sum())
-        am = view.argmax()
+        am = take(view.argmax())
         assert np.array_equal(am[clear], ref.pred[clear]), "argmax differs at a clear-margin row"
-        cerr = np.abs(view.conf() - ref.conf).max()
+        cerr = np.abs(take(view.conf()) - ref.conf).max()
         rep.max_conf_err = max(rep.max_conf_err, float(cerr))
         assert cerr <= 2e-2, f"confidence differs by {cerr}"
         self._argmax_fragile = bool((~clear).any())
@@ -77,15 +81,23 @@ class SideBySide:
         self._pending_ref = self.o.pending
 
     def step(self):
-        ref = self.o.block_forward()
-        view = self.bb.denoise_step([self.rid])
-        assert view.m_q == ref.window_rows
+        self.oracle_step()
+        self.check_step(self.bb.denoise_step([self.rid]))
+
+    def oracle_step(self):
+        self._pending_ref = self.o.block_forward()
+
+    def check_step(self, view):
+        """Compare this request's rows of a (possibly multi-request) step view."""
+        ref, mb = self._pending_ref, self.bb.limits.max_branches
         gbr, pos = view.rows()
+        mine = gbr // mb == self.rid
+        assert int(mine.sum()) == ref.window_rows
         lm = view.lm_rows()
-        assert np.array_equal(gbr[lm] % self.bb.limits.max_branches, ref.branch)
-        assert np.array_equal(pos[lm], ref.pos)
-        self._compare_forward(ref, view)
-        self._pending_ref = ref
+        sel = np.nonzero(mine[lm])[0]
+        assert np.array_equal(gbr[lm][sel] % mb, ref.branch)
+        assert np.array_equal(pos[lm][sel], ref.pos)
+        self._compare_forward(ref, view, sel)
         self.rep.steps += 1
 
     def refresh(self):
@@ -94,6 +106,10 @@ class SideBySide:
 
     # -- commit / merge / sync ------------------------------------------------------------------
     def commit(self):
+        self.oracle_commit()
+        return self.check_commit(self.bb.merge_commit([self.rid])[0])
+
+    def oracle_commit(self):
         o, rep, ref = self.o, self.rep, self._pending_ref
         p = o.p
         fragile = getattr(self, "_argmax_fragile", False)
@@ -138,8 +154,11 @@ class SideBySide:
         merges, syncs = o.merge_sync_all(prob)
         o.refresh_due = o.since_refresh >= p.refresh_interval and any(not b.done for b in o.br)
         rep.commits += len(commits); rep.merges += len(merges); rep.syncs += len(syncs)
+        self._last = (fragile, commits, merges, syncs)
 
-        st = self.bb.merge_commit([self.rid])[0]
+    def check_commit(self, st):
+        o, rep = self.o, self.rep
+        fragile, commits, merges, syncs = self._last
         X = self.bb.get_tokens(self.rid)
         same = np.array_equal(X, o.X)
         for k, b in enumerate(o.br):

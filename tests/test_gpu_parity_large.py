@@ -1,0 +1,110 @@
+"""Teacher-forced parity at the full shapes of the LLaDA-8B / Dream-7B class workloads.
+
+The oracle runs in fp32 here (fp64 copies of 7-8 G parameters do not fit comfortably); weights
+are generated on the GPU (bit-identical to the CPU generator) and copied to the host for it.
+Only a few steps are run per workload: one oracle block step is ~2 TFLOP of CPU work.
+"""
+import time
+import numpy as np
+import pytest
+import torch
+
+from workload import workload, gen_weights, gen_prompt
+from oracle.model import OracleModel
+from parity_harness import SideBySide, make_bb
+
+pytestmark = pytest.mark.gpu
+
+
+def setup(name, n_sample=None):
+    w = workload(name)
+    t = time.time()
+    weights = dict(gen_weights(w.model, w.seed, device="cuda:0"))
+    L = max(w.prompt_lens) + w.gen_len
+    bb = make_bb(w.model, w.decode, weights, len(w.block_sizes), L, w.gen_len,
+                 w.n_requests * sum(w.block_sizes), max_requests=w.n_requests)
+    host = {k: v.cpu() for k, v in weights.items()}
+    del weights
+    torch.cuda.empty_cache()
+    om = OracleModel(w.model, host, np.float32)
+    del host
+    print(f"[{name}] weights + oracle model ready in {time.time() - t:.1f}s", flush=True)
+    return w, bb, om
+
+
+def single_request(name, steps, refresh_after=None):
+    w, bb, om = setup(name)
+    try:
+        prompt = gen_prompt(w.model, w.seed, 0, w.prompt_lens[0])
+        s = SideBySide(bb, om, prompt, w.gen_len, w.block_sizes, w.decode)
+        t = time.time()
+        s.init()
+        print(f"[{name}] init compared in {time.time() - t:.1f}s: {s.rep}", flush=True)
+        s.compare_kv(0, 0)
+        s.compare_kv(len(w.block_sizes) - 1, w.model.n_layers - 1)
+        s.commit()
+        for i in range(steps):
+            if s.o.refresh_due or i == refresh_after:
+                s.refresh()
+                s.compare_kv(0, w.model.n_layers - 1)
+            t = time.time()
+            s.step()
+            s.commit()
+            print(f"[{name}] step {i} compared in {time.time() - t:.1f}s: {s.rep}", flush=True)
+        assert s.rep.max_logit_err <= 3e-2
+        return s
+    finally:
+        bb.close()
+
+
+def test_llada_8b_shape():
+    single_request("llada", steps=3, refresh_after=2)
+
+
+def test_dream_7b_shape():
+    single_request("dream", steps=2)
+
+
+def test_llada_long_context():
+    single_request("llada_long", steps=1)
+
+
+def test_llada_16_requests_sampled():
+    """All 16 requests run batched on the GPU; the oracle follows two of them."""
+    w, bb, om = setup("llada_x16")
+    try:
+        sampled = {}
+        for r, lp in enumerate(w.prompt_lens):
+            prompt = gen_prompt(w.model, w.seed, r, lp)
+            if r in (3, 13):
+                sampled[r] = SideBySide(bb, om, prompt, w.gen_len, w.block_sizes, w.decode)
+                assert sampled[r].rid == r
+            else:
+                assert bb.request_open(prompt, w.gen_len, w.block_sizes) == r
+        ids = list(range(w.n_requests))
+        from paper_2605_29233_amd import BB_INIT
+        for r in ids:
+            if r in sampled:
+                sampled[r].init()
+            else:
+                bb.refresh([r], BB_INIT)
+        for s in sampled.values():
+            s.oracle_commit()
+        stats = bb.merge_commit(ids)
+        for r, s in sampled.items():
+            s.check_commit(stats[r])
+        for i in range(2):
+            for s in sampled.values():
+                s.oracle_step()
+            view = bb.denoise_step(ids)
+            for s in sampled.values():
+                s.check_step(view)
+                s.oracle_commit()
+            stats = bb.merge_commit(ids)
+            for r, s in sampled.items():
+                s.check_commit(stats[r])
+            print(f"[llada_x16] step {i}: m_q={view.m_q} " + " | ".join(str(s.rep) for s in sampled.values()), flush=True)
+        for s in sampled.values():
+            assert s.rep.max_logit_err <= 3e-2
+    finally:
+        bb.close()
