@@ -1,0 +1,172 @@
+"""Throughput of the BlockBatch denoising path on one MI355X (LLaDA-8B-shaped synthetic model).
+
+A "step" is one pass of the whole hot path: bb_denoise_step (pack, batched block forward, LM
+head, vocabulary reduction) + bb_merge_commit (Eq. 1 commit, merge, sync), plus the periodic
+full-sequence refresh whenever R block forwards have run.  `value` is steps/s of a free-running
+decode (refreshes included, inputs and weights resident in HBM); the steady-state block forward,
+the refresh and the committed-token rate are reported beside it.  The roofline figure is for the
+weight-streaming MFMA GEMM launches of the block forward at a frozen, fully masked state, timed
+with HIP events on the library's stream; the CPU oracle is timed on the host for reference.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="llada")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every box has one); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from workload import workload, gen_weights, gen_prompt
+    from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT, BB_PERIODIC
+
+    w = workload(args.workload)
+    m = w.model
+    L = max(w.prompt_lens) + w.gen_len
+    step_rows = w.n_requests * sum(min(b, w.gen_len) for b in w.block_sizes)
+    torch.cuda.set_device(0)
+    bb = BlockBatch(m, w.decode, Limits(w.n_requests, len(w.block_sizes), L, w.gen_len, step_rows))
+    bb.load_weights(gen_weights(m, w.seed, device="cuda:0"))
+    torch.cuda.empty_cache()
+
+    def open_all():
+        ids = [bb.request_open(gen_prompt(m, w.seed, r, lp), w.gen_len, w.block_sizes) for r, lp in enumerate(w.prompt_lens)]
+        for r in ids:
+            bb.refresh([r], BB_INIT)
+        return ids
+
+    def decoded(stats):
+        return sum(st.branch[k].tokens_decoded for st in stats for k in range(st.n_branches))
+
+    R = w.decode.refresh_interval
+
+    # ---- 1. steady state at a frozen, fully masked state: block forward only --------------------
+    ids = open_all()
+    for _ in range(args.warmup):
+        bb.denoise_step(ids, want_view=False)
+    bb.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        bb.denoise_step(ids, want_view=False)
+    bb.synchronize()
+    fwd_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # ---- 2. per-kernel-class timing of the same frozen block forward (HIP events) ---------------
+    bb.profile_enable(True)
+    for _ in range(args.profile_steps):
+        bb.denoise_step(ids, want_view=False)
+    prof = bb.profile_read()
+    bb.profile_enable(False)
+    g = prof["gemm_skinny"] if prof["gemm_skinny"]["launches"] else prof["gemm_wide"]
+    gemm_ms = g["total_ms"] / max(g["launches"], 1)
+    gemm_gbs = g["bytes"] / 1e9 / (g["total_ms"] / 1e3) if g["total_ms"] > 0 else 0.0
+    gemm_tflops = g["flops"] / 1e12 / (g["total_ms"] / 1e3) if g["total_ms"] > 0 else 0.0
+    per_step = {k: v["total_ms"] / args.profile_steps for k, v in prof.items()}
+
+    # ---- 3. refresh alone --------------------------------------------------------------------------
+    bb.merge_commit(ids, want_stats=False)
+    bb.refresh(ids, BB_PERIODIC)
+    bb.synchronize()
+    t0 = time.perf_counter()
+    bb.refresh(ids, BB_PERIODIC)
+    bb.synchronize()
+    refresh_ms = (time.perf_counter() - t0) * 1e3
+
+    # ---- 4. free-running decode: the timed region ---------------------------------------------------
+    since = 0
+
+    def one_step():
+        nonlocal since
+        bb.denoise_step(ids, want_view=False)
+        bb.merge_commit(ids, want_stats=False)
+        since += 1
+        if since >= R:
+            bb.refresh(ids, BB_PERIODIC)
+            since = 0
+
+    for _ in range(args.warmup):
+        one_step()
+    s0 = [bb.get_stats(r) for r in ids]
+    bb.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    bb.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    s1 = [bb.get_stats(r) for r in ids]
+    finished_early = any(st.all_done for st in s1)
+    n_refresh = sum(b.nfe_refresh - a.nfe_refresh for a, b in zip(s0, s1)) // max(len(ids), 1)
+    committed = decoded(s1) - decoded(s0)
+    ms_per_step = dt * 1e3 / args.steps
+
+    out = {
+        "metric": "branch-batched denoise steps/s (free-running, refreshes included), LLaDA-8B shape, 1 MI355X",
+        "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights x (bf16 hi+lo) activations, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "model_shape": m.name, "requests": w.n_requests, "prompt_len": list(w.prompt_lens),
+                   "gen_len": w.gen_len, "block_sizes": list(w.block_sizes), "packed_rows": step_rows,
+                   "refresh_interval": R, "tau_dec": w.decode.tau_dec},
+        "committed_tokens_per_s": committed / dt, "committed_tokens": committed, "refreshes_in_timed_region": int(n_refresh),
+        "finished_early": bool(finished_early),
+        "block_forward_ms_steady": fwd_ms, "block_forward_steps_per_s_steady": 1e3 / fwd_ms, "refresh_ms": refresh_ms,
+        "kernel_ms_per_block_forward": per_step,
+        "roofline": {"bound": "hbm", "kernel": "gemm_kernel (weight-streaming MFMA GEMM, block forward)",
+                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "avg_launch_ms": gemm_ms, "launches": g["launches"],
+                     "mfma_tflops": gemm_tflops, "mfma_frac_of_bf16_peak": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
+    }
+    bb.close()
+    del bb
+    torch.cuda.empty_cache()
+
+    # ---- 5. the CPU oracle on the host cores (reported baseline, bounded sample) ----------------------
+    if not args.no_cpu_baseline:
+        from oracle.model import OracleModel
+        from oracle.blockbatch import OracleRequest
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        host = {k: v.cpu() for k, v in gen_weights(m, w.seed, device="cuda:0")}
+        om = OracleModel(m, host, np.float32)
+        del host
+        rq = OracleRequest(om, gen_prompt(m, w.seed, 0, w.prompt_lens[0]), w.gen_len, w.block_sizes, w.decode)
+        rq.init_forward()
+        rq.commit_merge()
+        n_cpu, t0 = 0, time.perf_counter()
+        while n_cpu < 3 or (time.perf_counter() - t0 < 10 and n_cpu < 12):
+            rq.block_forward()
+            rq.commit_merge()
+            n_cpu += 1
+        cdt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": n_cpu / cdt, "unit": "steps/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"{n_cpu} block steps (block forward + commit/merge, no refresh) of request 0 "
+                                         f"after the initial forward, fp32 numpy oracle"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -174,6 +174,26 @@ int bb_get_kv(bb_ctx* ctx, int req_id, int branch, int layer, float* K_host, flo
 /* Plain device-to-host copy after a stream synchronise (for the pointers of bb_step_view). */
 int bb_read_device(bb_ctx* ctx, const void* src_dev, void* dst_host, size_t bytes);
 int bb_synchronize(bb_ctx* ctx);
+/* ---- measurement: per-kernel-class timing with HIP events on the context's stream ---------
+ * While enabled, every kernel launch of the forward is bracketed by two events (which
+ * perturbs the timeline slightly: use it for per-kernel figures, not for end-to-end rates).
+ * bb_profile_read waits for the stream, aggregates the recorded launches per class, copies
+ * up to max_entries classes to out_host, returns their number in *n_out and resets. */
+#define BB_K_GEMM_SKINNY 0   /* MFMA GEMM launches with <= 256 activation rows (weight streaming) */
+#define BB_K_GEMM_WIDE   1   /* MFMA GEMM launches with  > 256 activation rows                     */
+#define BB_K_ATTENTION   2
+#define BB_K_GLUE        3   /* embedding, norms, RoPE/KV write, SwiGLU, vocabulary reduction, packing */
+#define BB_K_POLICY      4   /* commit / merge / sync and page copies                                */
+#define BB_K_CLASSES     5
+typedef struct {
+    int klass, launches;
+    double total_ms;
+    double bytes;            /* algorithmic bytes: weights streamed (GEMM), K/V read (attention)     */
+    double flops;            /* algorithmic flops of the contraction (GEMM, attention)               */
+} bb_profile_entry;
+int bb_profile_enable(bb_ctx* ctx, int on);
+int bb_profile_read(bb_ctx* ctx, bb_profile_entry* out_host, int max_entries, int* n_out);
+
 /* C[M][N] = A[M][K] . W[N][K]^T through the same packing, tiling and MFMA kernels the
  * forward uses (kernel-level parity test).  A_host fp32, W_host bf16 bits, C_host fp32;
  * split_k = 0 lets the library choose. */

@@ -63,7 +63,12 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read")
+KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
+
+
+class bb_profile_entry(C.Structure):
+    _fields_ = [("klass", C.c_int), ("launches", C.c_int), ("total_ms", C.c_double), ("bytes", C.c_double), ("flops", C.c_double)]
 
 
 def load_library():
@@ -94,6 +99,8 @@ def load_library():
         lib.bb_get_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         lib.bb_read_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         lib.bb_synchronize.argtypes = [C.c_void_p]
+        lib.bb_profile_enable.argtypes = [C.c_void_p, C.c_int]
+        lib.bb_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]
         lib.bb_debug_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         _LIB = lib
     return _LIB
@@ -235,6 +242,17 @@ class BlockBatch:
     # -- inspection ---------------------------------------------------------------------------
     def synchronize(self):
         self._chk(self.lib.bb_synchronize(self._ctx), "bb_synchronize")
+
+    def profile_enable(self, on=True):
+        self._chk(self.lib.bb_profile_enable(self._ctx, int(on)), "bb_profile_enable")
+
+    def profile_read(self):
+        """{class name: dict(launches, total_ms, bytes, flops)} of the launches recorded since the last read."""
+        arr = (bb_profile_entry * len(KERNEL_CLASSES))()
+        n = C.c_int(0)
+        self._chk(self.lib.bb_profile_read(self._ctx, C.cast(arr, C.c_void_p), len(KERNEL_CLASSES), C.byref(n)), "bb_profile_read")
+        return {KERNEL_CLASSES[e.klass]: dict(launches=e.launches, total_ms=e.total_ms, bytes=e.bytes, flops=e.flops)
+                for e in list(arr)[:n.value]}
 
     def get_tokens(self, rid):
         n, L = self._req[rid]

@@ -33,7 +33,28 @@ struct bb_ctx {
     char* d_stats;                      // device staging for stats copies
     std::string err;
     int last_forward_rows, last_lm_cap;
+    // per-launch event timing (bb_profile_*)
+    int prof_on;
+    struct ProfRec { hipEvent_t a, b; int klass; double bytes, flops; };
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> ev_pool;
 };
+
+// Bracket one launch with events when profiling is on.
+struct ProfScope {
+    bb_ctx* c; int idx;
+    ProfScope(bb_ctx* c_, int klass, double bytes, double flops) : c(c_), idx(-1) {
+        if (!c->prof_on) return;
+        auto get = [&]() { hipEvent_t e; if (c->ev_pool.empty()) { if (hipEventCreate(&e) != hipSuccess) return (hipEvent_t) nullptr; }
+                           else { e = c->ev_pool.back(); c->ev_pool.pop_back(); } return e; };
+        bb_ctx::ProfRec r{get(), get(), klass, bytes, flops};
+        if (!r.a || !r.b) return;
+        (void)hipEventRecord(r.a, c->stream);
+        c->prof.push_back(r); idx = (int)c->prof.size() - 1;
+    }
+    ~ProfScope() { if (idx >= 0) (void)hipEventRecord(c->prof[idx].b, c->stream); }
+};
+#define PROF(klass, bytes, flops) ProfScope prof_scope_(c, klass, bytes, flops)
 
 static int fail(bb_ctx* c, int code, const std::string& msg) { if (c) c->err = msg; return code; }
 #define HIPCHK(c, expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) \
@@ -206,7 +227,9 @@ extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decod
 
 extern "C" int bb_destroy(bb_ctx* ctx) {
     if (!ctx) return BB_EINVAL;
-    hipStreamSynchronize(ctx->stream);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (auto e : ctx->ev_pool) (void)hipEventDestroy(e);
     delete ctx;
     return BB_OK;
 }
@@ -355,32 +378,44 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const bb_model_cfg& m = c->m; const Dev& D = c->D; hipStream_t s = c->stream;
     const int d = m.d_model, nq = m.n_q_heads * m.head_dim, f = m.d_ffn, nqkv = D.nqkv;
     const int mt = (rows_cap + 31) / 32, rows_pad = mt * 32;
-    launch_embed(D, c->emb, c->h, rows_cap, s);
+    const int gk = rows_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
+    auto gemm = [&](const u32x4* W, float* C, int N, int K, int rows, int mtt, GemmPlan p, int klass) {
+        PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
+        launch_gemm(W, c->Apk, C, mtt, N, K, p, N, (size_t)mtt * 32 * N, s);
+    };
+    { PROF(BB_K_GLUE, 0, 0); launch_embed(D, c->emb, c->h, rows_cap, s); }
     GemmPlan p_down{1, 0};
     for (int li = 0; li < m.n_layers; ++li) {
         const LayerW& W = c->layers[li];
         const size_t pstride = (size_t)rows_pad * d;
-        launch_rmsnorm_pack(D, c->h, c->part, li ? p_down.split_k : 0, pstride, W.g_attn, c->Apk, rows_cap, mt, 0, 0, s);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_rmsnorm_pack(D, c->h, c->part, li ? p_down.split_k : 0, pstride, W.g_attn, c->Apk, rows_cap, mt, 0, 0, s); }
         GemmPlan p = gemm_plan(rows_cap, nqkv, d, 0);
-        launch_gemm(W.wqkv, c->Apk, c->qkv, mt, nqkv, d, p, nqkv, (size_t)rows_pad * nqkv, s);
-        launch_rope_kv(D, c->qkv, p.split_k, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s);
+        gemm(W.wqkv, c->qkv, nqkv, d, rows_cap, mt, p, gk);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_rope_kv(D, c->qkv, p.split_k, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s); }
         if (mode == 2 && li == m.n_layers - 1) break;
-        launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, s);
+        { // K,V bytes one pass over each segment's cache row would read (two fp16 terms each)
+          PROF(BB_K_ATTENTION, 0, 0);
+          launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, s); }
         p = gemm_plan(rows_cap, d, nq, 0);
-        launch_gemm(W.wo, c->Apk, c->part, mt, d, nq, p, d, pstride, s);
-        launch_rmsnorm_pack(D, c->h, c->part, p.split_k, pstride, W.g_ffn, c->Apk, rows_cap, mt, 0, 0, s);
+        gemm(W.wo, c->part, d, nq, rows_cap, mt, p, gk);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_rmsnorm_pack(D, c->h, c->part, p.split_k, pstride, W.g_ffn, c->Apk, rows_cap, mt, 0, 0, s); }
         p = gemm_plan(rows_cap, 2 * f, d, 0);
-        launch_gemm(W.wgu, c->Apk, c->gu, mt, 2 * f, d, p, 2 * f, (size_t)rows_pad * 2 * f, s);
-        launch_swiglu_pack(D, c->gu, p.split_k, (size_t)rows_pad * 2 * f, c->Apk, rows_cap, mt, s);
+        gemm(W.wgu, c->gu, 2 * f, d, rows_cap, mt, p, gk);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_swiglu_pack(D, c->gu, p.split_k, (size_t)rows_pad * 2 * f, c->Apk, rows_cap, mt, s); }
         p_down = gemm_plan(rows_cap, d, f, 0);
-        launch_gemm(W.wdown, c->Apk, c->part, mt, d, f, p_down, d, pstride, s);
+        gemm(W.wdown, c->part, d, f, rows_cap, mt, p_down, gk);
     }
     if (mode != 2) {
         const int mt_lm = (lm_cap + 31) / 32;
-        launch_rmsnorm_pack(D, c->h, c->part, p_down.split_k, (size_t)rows_pad * d, c->g_final, c->Apk, lm_cap, mt_lm, 1, mode == 1, s);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_rmsnorm_pack(D, c->h, c->part, p_down.split_k, (size_t)rows_pad * d, c->g_final, c->Apk, lm_cap, mt_lm, 1, mode == 1, s); }
         GemmPlan p = gemm_plan(lm_cap, m.vocab, d, 1);
-        launch_gemm(c->lm, c->Apk, c->logits, mt_lm, m.vocab, d, p, m.vocab, 0, s);
-        launch_vocab_reduce(D, c->logits, lm_cap, mode == 1, s);
+        gemm(c->lm, c->logits, m.vocab, d, lm_cap, mt_lm, p, lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE);
+        { PROF(BB_K_GLUE, 0, 0); launch_vocab_reduce(D, c->logits, lm_cap, mode == 1, s); }
     }
     c->last_forward_rows = rows_cap; c->last_lm_cap = lm_cap;
     HIPCHK(c, hipGetLastError());
@@ -426,8 +461,8 @@ extern "C" int bb_denoise_step(bb_ctx* c, const int* ids, int n, bb_step_view* v
     }
     if (rows > c->lim.max_step_rows) return fail(c, BB_ENOMEM, "step rows exceed max_step_rows");
     if ((rc = upload_req_list(c, ids, n)) != BB_OK) return rc;
-    launch_pack_step(c->D, n, c->stream);
-    launch_page_copies(c->D, c->stream);
+    { PROF(BB_K_GLUE, 0, 0); launch_pack_step(c->D, n, c->stream); }
+    { PROF(BB_K_POLICY, 0, 0); launch_page_copies(c->D, c->stream); }
     rc = forward(c, rows, rows, 0, 0, c->D.max_req * c->D.max_br, maxb);
     if (rc == BB_OK && view) fill_view(c, view);
     return rc;
@@ -448,7 +483,7 @@ extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stat
     int rc = check_reqs(c, ids, n, true);
     if (rc != BB_OK) return rc;
     if ((rc = upload_req_list(c, ids, n)) != BB_OK) return rc;
-    launch_commit_merge(c->D, n, reinterpret_cast<const uint16_t*>(c->lm), c->stream);
+    { PROF(BB_K_POLICY, 0, 0); launch_commit_merge(c->D, n, reinterpret_cast<const uint16_t*>(c->lm), c->stream); }
     HIPCHK(c, hipGetLastError());
     if (stats) {
         HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -460,6 +495,31 @@ extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stat
 // ---- inspection and teacher forcing ---------------------------------------------------------------------
 static int check_one(bb_ctx* c, int id) {
     if (!c || id < 0 || id >= c->lim.max_requests || !c->reqs[id].in_use) return BB_EINVAL;
+    return BB_OK;
+}
+
+extern "C" int bb_profile_enable(bb_ctx* c, int on) {
+    if (!c) return BB_EINVAL;
+    c->prof_on = on != 0;
+    return BB_OK;
+}
+
+extern "C" int bb_profile_read(bb_ctx* c, bb_profile_entry* out, int max_entries, int* n_out) {
+    if (!c || !out || !n_out || max_entries < 1) return BB_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    bb_profile_entry acc[BB_K_CLASSES];
+    for (int k = 0; k < BB_K_CLASSES; ++k) acc[k] = bb_profile_entry{k, 0, 0.0, 0.0, 0.0};
+    for (auto& r : c->prof) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
+            acc[r.klass].launches += 1; acc[r.klass].total_ms += ms; acc[r.klass].bytes += r.bytes; acc[r.klass].flops += r.flops;
+        }
+        c->ev_pool.push_back(r.a); c->ev_pool.push_back(r.b);
+    }
+    c->prof.clear();
+    int n = 0;
+    for (int k = 0; k < BB_K_CLASSES && n < max_entries; ++k) out[n++] = acc[k];
+    *n_out = n;
     return BB_OK;
 }
 

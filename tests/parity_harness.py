@@ -59,7 +59,7 @@ class SideBySide:
         keep = np.arange(lg.shape[1]) != self.o.mask_id
         err = np.abs(lg[:, keep] - ref.logits[:, keep]).max()
         rep.max_logit_err = max(rep.max_logit_err, float(err))
-        rep.rows += view.m_lm
+        rep.rows += n_mine
         assert err <= LOGIT_TOL, f"logits differ by {err}"
         srt = np.sort(ref.logits[:, keep], axis=1)
         margin = srt[:, -1] - srt[:, -2]
