@@ -26,9 +26,9 @@ struct bb_ctx {
     int n_expected;
     // activations
     float *h, *qkv, *part, *gu, *logits, *dbg;
-    u32x4* Apk; half_t* Q; char* stage;
+    u32x4 *Apk, *Apk2; half_t* Q; char* stage;     // Apk2: SwiGLU output panel (written while Apk is still being read)
     size_t qkv_elems, part_elems, gu_elems, stage_bytes, dbg_bytes;
-    int refresh_rows_cap;
+    int refresh_rows_cap, ngu;
     std::vector<HostReq> reqs;
     char* d_stats;                      // device staging for stats copies
     std::string err;
@@ -137,18 +137,21 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.out_pred = b.take<int>(lm_pad); D.out_conf = b.take<float>(lm_pad); D.out_lse = b.take<float>(lm_pad);
     D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
     D.req_list = b.take<int>(l.max_requests);
+    D.tile_counters = b.take<int>(BB_TILE_COUNTERS);
     c->d_stats = b.take<char>(sizeof(ReqHeader) + sizeof(bb_branch_state) * BB_MAX_BRANCHES);
     D.Kc = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
     D.Vt = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
     size_t state_end = align_up(b.off, 256);
     // activations
     const int kmax = std::max(std::max(m.d_model, m.d_ffn), nq);
+    c->ngu = (m.d_ffn + 127) / 128 * 256;          // fused gate/up rows: 128 gate + 128 up per 256-column tile
     c->h = b.take<float>((size_t)rows_pad * m.d_model);
     c->Apk = b.take<u32x4>((size_t)rows_pad * kmax / 8 * BB_SPLIT);
+    c->Apk2 = b.take<u32x4>((size_t)rows_pad * m.d_ffn / 8 * BB_SPLIT);
     c->Q = b.take<half_t>((size_t)rows_pad * nq * 2);
     c->qkv_elems = buf_elems(rows_cap, nqkv, m.d_model);
     c->part_elems = std::max(buf_elems(rows_cap, m.d_model, nq), buf_elems(rows_cap, m.d_model, m.d_ffn));
-    c->gu_elems = buf_elems(rows_cap, 2 * m.d_ffn, m.d_model);
+    c->gu_elems = buf_elems(rows_cap, c->ngu, m.d_model);
     c->qkv = b.take<float>(c->qkv_elems);
     c->part = b.take<float>(c->part_elems);
     c->gu = b.take<float>(c->gu_elems);
@@ -168,7 +171,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     for (auto& L : c->layers) {
         L.wqkv = b.take<u32x4>((size_t)nqkv * m.d_model / 8);
         L.wo = b.take<u32x4>((size_t)m.d_model * nq / 8);
-        L.wgu = b.take<u32x4>((size_t)2 * m.d_ffn * m.d_model / 8);
+        L.wgu = b.take<u32x4>((size_t)c->ngu * m.d_model / 8);
         L.wdown = b.take<u32x4>((size_t)m.d_model * m.d_ffn / 8);
         L.g_attn = b.take<float>(m.d_model); L.g_ffn = b.take<float>(m.d_model);
         L.bqkv = b.take<float>(nqkv);
@@ -207,6 +210,10 @@ extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decod
     // otherwise reach 0 * NaN in the attention's P.V product)
     size_t zero_bytes = (char*)c->emb - c->ws;
     hipError_t e = hipMemsetAsync(c->ws, 0, zero_bytes, c->stream);
+    if (e != hipSuccess) { delete c; return BB_EHIP; }
+    if (model->d_ffn % 128)                              // padded gate/up rows must be finite
+        for (auto& L : c->layers)
+            if (e == hipSuccess) e = hipMemsetAsync(L.wgu, 0, (size_t)c->ngu * model->d_model * 2, c->stream);
     if (e != hipSuccess) { delete c; return BB_EHIP; }
     // rotary table in double precision on the host
     const int half = model->head_dim / 2, lpad = c->D.lpad;
@@ -264,7 +271,7 @@ static int load_one(bb_ctx* c, const bb_tensor& t) {
         if (ok) HIPCHK(c, hipMemcpyAsync(c->emb, src, bytes, hipMemcpyDeviceToDevice, c->stream));
     } else if (name == "lm_head") {
         slot = 1; ok = expect(m.vocab, d);
-        if (ok) launch_tile_weights(src, m.vocab, d, c->lm, 0, c->stream);
+        if (ok) launch_tile_weights(src, m.vocab, d, c->lm, 0, 0, c->stream);
     } else if (name == "final_norm") {
         slot = 2; ok = t.rows * t.cols == d;
         if (ok) widen(c->g_final, d);
@@ -282,17 +289,17 @@ static int load_one(bb_ctx* c, const bb_tensor& t) {
         slot = 3 + li * 12 + ki;
         switch (ki) {
             case 0: ok = t.rows * t.cols == d; if (ok) widen(L.g_attn, d); break;
-            case 1: ok = expect(nq, d); if (ok) launch_tile_weights(src, nq, d, L.wqkv, 0, c->stream); break;
-            case 2: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq, c->stream); break;
-            case 3: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq + nkv, c->stream); break;
+            case 1: ok = expect(nq, d); if (ok) launch_tile_weights(src, nq, d, L.wqkv, 0, 0, c->stream); break;
+            case 2: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq, 0, c->stream); break;
+            case 3: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq + nkv, 0, c->stream); break;
             case 4: ok = m.qkv_bias && t.rows * t.cols == nq; if (ok) widen(L.bqkv, nq); break;
             case 5: ok = m.qkv_bias && t.rows * t.cols == nkv; if (ok) widen(L.bqkv + nq, nkv); break;
             case 6: ok = m.qkv_bias && t.rows * t.cols == nkv; if (ok) widen(L.bqkv + nq + nkv, nkv); break;
-            case 7: ok = expect(d, nq); if (ok) launch_tile_weights(src, d, nq, L.wo, 0, c->stream); break;
+            case 7: ok = expect(d, nq); if (ok) launch_tile_weights(src, d, nq, L.wo, 0, 0, c->stream); break;
             case 8: ok = t.rows * t.cols == d; if (ok) widen(L.g_ffn, d); break;
-            case 9: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 0, c->stream); break;
-            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, f, c->stream); break;
-            case 11: ok = expect(d, f); if (ok) launch_tile_weights(src, d, f, L.wdown, 0, c->stream); break;
+            case 9: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 0, 1, c->stream); break;
+            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 128, 1, c->stream); break;
+            case 11: ok = expect(d, f); if (ok) launch_tile_weights(src, d, f, L.wdown, 0, 0, c->stream); break;
         }
     } else return fail(c, BB_EINVAL, "unknown tensor " + name);
     if (!ok) return fail(c, BB_EINVAL, "shape mismatch for " + name);
@@ -376,45 +383,34 @@ static int check_reqs(bb_ctx* c, const int* ids, int n, bool need_init) {
 // (results broadcast to all branches); 2: cache-only refresh (stops after the last K,V write).
 static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, int n_segs, int max_seg_rows) {
     const bb_model_cfg& m = c->m; const Dev& D = c->D; hipStream_t s = c->stream;
-    const int d = m.d_model, nq = m.n_q_heads * m.head_dim, f = m.d_ffn, nqkv = D.nqkv;
+    const int d = m.d_model, nq = m.n_q_heads * m.head_dim, f = m.d_ffn, nqkv = D.nqkv, ngu = c->ngu;
     const int mt = (rows_cap + 31) / 32, rows_pad = mt * 32;
     const int gk = rows_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
-    auto gemm = [&](const u32x4* W, float* C, int N, int K, int rows, int mtt, GemmPlan p, int klass) {
+    auto gemm = [&](int epi, EpiArgs E, const u32x4* W, const u32x4* A, float* P, int N, int K, int rows, int mtt, int klass, int force) {
+        GemmPlan p = gemm_plan(rows, N, K, force);
+        E.P = P; E.ldp = N; E.split_stride = (size_t)mtt * 32 * N; E.counters = D.tile_counters;
         PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-        launch_gemm(W, c->Apk, C, mtt, N, K, p, N, (size_t)mtt * 32 * N, s);
+        launch_gemm(D, epi, E, W, A, mtt, N, K, p, s);
     };
+    EpiArgs E0; memset(&E0, 0, sizeof(E0));
+    E0.m_count = D.counts; E0.h = c->h; E0.ldh = d; E0.Apk = c->Apk2; E0.mt_total = mt; E0.f = f; E0.Q = c->Q;
     { PROF(BB_K_GLUE, 0, 0); launch_embed(D, c->emb, c->h, rows_cap, s); }
-    GemmPlan p_down{1, 0};
     for (int li = 0; li < m.n_layers; ++li) {
         const LayerW& W = c->layers[li];
-        const size_t pstride = (size_t)rows_pad * d;
-        { PROF(BB_K_GLUE, 0, 0);
-          launch_rmsnorm_pack(D, c->h, c->part, li ? p_down.split_k : 0, pstride, W.g_attn, c->Apk, rows_cap, mt, 0, 0, s); }
-        GemmPlan p = gemm_plan(rows_cap, nqkv, d, 0);
-        gemm(W.wqkv, c->qkv, nqkv, d, rows_cap, mt, p, gk);
-        { PROF(BB_K_GLUE, 0, 0);
-          launch_rope_kv(D, c->qkv, p.split_k, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s); }
+        EpiArgs E = E0; E.layer = li; E.bias = m.qkv_bias ? W.bqkv : nullptr;
+        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, W.g_attn, c->Apk, mt, 0, 0, s); }
+        gemm(EPI_QKV, E, W.wqkv, c->Apk, c->qkv, nqkv, d, rows_cap, mt, gk, 0);
         if (mode == 2 && li == m.n_layers - 1) break;
-        { // K,V bytes one pass over each segment's cache row would read (two fp16 terms each)
-          PROF(BB_K_ATTENTION, 0, 0);
-          launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, s); }
-        p = gemm_plan(rows_cap, d, nq, 0);
-        gemm(W.wo, c->part, d, nq, rows_cap, mt, p, gk);
-        { PROF(BB_K_GLUE, 0, 0);
-          launch_rmsnorm_pack(D, c->h, c->part, p.split_k, pstride, W.g_ffn, c->Apk, rows_cap, mt, 0, 0, s); }
-        p = gemm_plan(rows_cap, 2 * f, d, 0);
-        gemm(W.wgu, c->gu, 2 * f, d, rows_cap, mt, p, gk);
-        { PROF(BB_K_GLUE, 0, 0);
-          launch_swiglu_pack(D, c->gu, p.split_k, (size_t)rows_pad * 2 * f, c->Apk, rows_cap, mt, s); }
-        p_down = gemm_plan(rows_cap, d, f, 0);
-        gemm(W.wdown, c->part, d, f, rows_cap, mt, p_down, gk);
+        { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, s); }
+        gemm(EPI_RESID, E, W.wo, c->Apk, c->part, d, nq, rows_cap, mt, gk, 0);
+        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, W.g_ffn, c->Apk, mt, 0, 0, s); }
+        gemm(EPI_SWIGLU, E, W.wgu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, 0);
+        gemm(EPI_RESID, E, W.wdown, c->Apk2, c->part, d, f, rows_cap, mt, gk, 0);
     }
     if (mode != 2) {
         const int mt_lm = (lm_cap + 31) / 32;
-        { PROF(BB_K_GLUE, 0, 0);
-          launch_rmsnorm_pack(D, c->h, c->part, p_down.split_k, (size_t)rows_pad * d, c->g_final, c->Apk, lm_cap, mt_lm, 1, mode == 1, s); }
-        GemmPlan p = gemm_plan(lm_cap, m.vocab, d, 1);
-        gemm(c->lm, c->logits, m.vocab, d, lm_cap, mt_lm, p, lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE);
+        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->g_final, c->Apk, mt_lm, 1, mode == 1, s); }
+        gemm(EPI_NONE, E0, c->lm, c->Apk, c->logits, m.vocab, d, lm_cap, mt_lm, lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE, 1);
         { PROF(BB_K_GLUE, 0, 0); launch_vocab_reduce(D, c->logits, lm_cap, mode == 1, s); }
     }
     c->last_forward_rows = rows_cap; c->last_lm_cap = lm_cap;
@@ -603,9 +599,11 @@ extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float
     if (b.off > (size_t)((char*)c->emb - (char*)c->h)) return fail(c, BB_ENOMEM, "debug gemm does not fit the activation region");
     HIPCHK(c, hipMemcpyAsync(dA, A, (size_t)M * K * 4, hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, hipMemcpyAsync(dW, W, (size_t)N * K * 2, hipMemcpyHostToDevice, c->stream));
-    launch_tile_weights(dW, N, K, dWt, 0, c->stream);
+    launch_tile_weights(dW, N, K, dWt, 0, 0, c->stream);
     launch_pack_rows(dA, M, K, dAp, mt, c->stream);
-    launch_gemm(dWt, dAp, dC, mt, N, K, p, N, (size_t)rows_pad * N, c->stream);
+    EpiArgs E; memset(&E, 0, sizeof(E));
+    E.P = dC; E.ldp = N; E.split_stride = (size_t)rows_pad * N; E.counters = c->D.tile_counters; E.m_count = c->D.counts;
+    launch_gemm(c->D, EPI_NONE, E, dWt, dAp, mt, N, K, p, c->stream);
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipStreamSynchronize(c->stream));
     std::vector<float> tmp(c_elems);

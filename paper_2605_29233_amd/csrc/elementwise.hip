@@ -1,6 +1,6 @@
-// Memory-bound glue kernels of the forward: embedding gather, RMSNorm (+ residual add of the
-// previous GEMM's split-K partial sums) with packing into MFMA fragments, RoPE + KV-cache
-// write, SwiGLU, and the online-softmax vocabulary reduction.
+// Memory-bound glue kernels of the forward: embedding gather, RMSNorm with packing into MFMA
+// fragments, and the online-softmax vocabulary reduction.  (Residual adds, SwiGLU, RoPE and
+// the cache write live in the GEMM epilogues.)
 #include "bb_internal.h"
 
 static __device__ __forceinline__ float wg_sum(float v, float* sh) {
@@ -49,32 +49,24 @@ void launch_embed(const Dev& D, const uint16_t* emb, float* h, int rows_cap, hip
 }
 
 // One workgroup per destination row j of the packed panel.  Source row r = j, or the j-th
-// masked row when gather != 0 (LM-head panel).  h[r] += sum_s partial[s][r] first (the residual
-// add of the preceding O / down projection), then y = h / sqrt(mean(h^2) + eps) * gain.
+// masked row when gather != 0 (LM-head panel).  y = h / sqrt(mean(h^2) + eps) * gain.
 // In gather mode y is also stored as the branch's probability-map entry for that position
 // (P_k(i, v) = exp(y . W_v - lse) is evaluated on demand by the merge), for every branch of
 // the request when bcast != 0 (initial forward: all rows are identical).
-__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restrict__ h, const float* __restrict__ partial,
-                                                           int n_partial, size_t partial_stride,
-                                                           const float* __restrict__ gain, u32x4* __restrict__ Apk,
-                                                           int mt_total, int gather, int bcast) {
+__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, const float* __restrict__ h, const float* __restrict__ gain,
+                                                           u32x4* __restrict__ Apk, int mt_total, int gather, int bcast) {
     __shared__ float sh[4];
     const int j = blockIdx.x, d = D.d, k8s = d >> 3;
     const int count = gather ? D.counts[1] : D.counts[0];
     if (j >= count) { zero_packed_row(Apk, j, k8s, mt_total); return; }
     const int r = gather ? D.lm_row[j] : j;
-    float* hr = h + (size_t)r * d;
+    const float* hr = h + (size_t)r * d;
     float ss = 0.f;
     for (int k4 = threadIdx.x; k4 < (d >> 2); k4 += blockDim.x) {
-        float4 v = reinterpret_cast<float4*>(hr)[k4];
-        for (int s = 0; s < n_partial; ++s) {
-            float4 p = reinterpret_cast<const float4*>(partial + s * partial_stride + (size_t)r * d)[k4];
-            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-        }
-        if (n_partial) reinterpret_cast<float4*>(hr)[k4] = v;
+        const float4 v = reinterpret_cast<const float4*>(hr)[k4];
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
-    ss = wg_sum(ss, sh);            // also orders the writes to hr before the reads below
+    ss = wg_sum(ss, sh);
     const float inv = 1.0f / sqrtf(ss / (float)d + D.rms_eps);
     int gbr = 0, nb = 1; size_t mrow = 0;
     if (gather) {
@@ -98,89 +90,9 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restr
     }
 }
 
-void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
-                         const float* gain, u32x4* Apk, int rows_cap, int mt_total, int gather, int bcast,
+void launch_rmsnorm_pack(const Dev& D, const float* h, const float* gain, u32x4* Apk, int mt_total, int gather, int bcast,
                          hipStream_t s) {
-    (void)rows_cap;
-    rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, gather, bcast);
-}
-
-// q,k,v = sum of split-K partials (+ bias); rotate q and k by the row's absolute position
-// (pairs (j, j + hd/2), angle pos * base^(-2j/hd), from a host-computed table); write q for
-// the attention kernel, k into the row's cache page and v into the transposed cache, each as
-// two fp16 terms hi + lo.
-__global__ __launch_bounds__(256) void rope_kv_kernel(Dev D, const float* __restrict__ qkv, int n_partial,
-                                                      size_t partial_stride, const float* __restrict__ bias,
-                                                      half_t* __restrict__ Q, int layer) {
-    const int row = blockIdx.x;
-    if (row >= D.counts[0]) return;
-    const int hd = D.hd, half = hd >> 1, pos = D.row_pos[row], phys = D.row_phys[row];
-    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
-    const float* src = qkv + (size_t)row * D.nqkv;
-    const float* cs = D.rope_cos + (size_t)pos * half;
-    const float* sn = D.rope_sin + (size_t)pos * half;
-    auto val = [&](int c) {
-        float v = bias ? bias[c] : 0.f;
-        for (int s = 0; s < n_partial; ++s) v += src[s * partial_stride + c];
-        return v;
-    };
-    const int nq = D.hq * half, nk = D.hkv * half;
-    auto put = [](half_t* hi_p, half_t* lo_p, float y) {
-        const half_t hi = (half_t)y;
-        *hi_p = hi;
-        *lo_p = (half_t)(y - (float)hi);
-    };
-    for (int idx = threadIdx.x; idx < nq + nk; idx += blockDim.x) {
-        const bool isq = idx < nq;
-        const int e = isq ? idx : idx - nq;
-        const int head = e / half, j = e % half;
-        const int c0 = (isq ? 0 : D.hq * hd) + head * hd + j;
-        const float x1 = val(c0), x2 = val(c0 + half), c = cs[j], s = sn[j];
-        const float y1 = x1 * c - x2 * s, y2 = x2 * c + x1 * s;
-        // both layouts: [.. head][term][hd]
-        half_t* dst = isq ? Q + ((size_t)row * D.hq + head) * 2 * hd
-                          : D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + pos) * D.hkv + head) * 2 * hd;
-        put(dst + j, dst + hd + j, y1);
-        put(dst + j + half, dst + hd + j + half, y2);
-    }
-    const int voff = (D.hq + D.hkv) * hd;
-    for (int e = threadIdx.x; e < D.hkv * hd; e += blockDim.x) {
-        const int head = e / hd, dd = e % hd;
-        half_t* base = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + head) * 2 * hd * (size_t)D.lpad;
-        put(base + (size_t)dd * D.lpad + pos, base + (size_t)(hd + dd) * D.lpad + pos, val(voff + e));
-    }
-}
-
-void launch_rope_kv(const Dev& D, const float* qkv, int n_partial, size_t partial_stride, const float* bias,
-                    half_t* Q, int layer, int rows_cap, hipStream_t s) {
-    rope_kv_kernel<<<rows_cap, 256, 0, s>>>(D, qkv, n_partial, partial_stride, bias, Q, layer);
-}
-
-// act = SiLU(gate) * up, gate = columns [0, F), up = columns [F, 2F) of the fused projection.
-__global__ void swiglu_pack_kernel(Dev D, const float* __restrict__ gu, int n_partial, size_t partial_stride,
-                                   u32x4* __restrict__ Apk, int mt_total) {
-    const int j = blockIdx.x, f = D.f, k8s = f >> 3;
-    if (j >= D.counts[0]) { zero_packed_row(Apk, j, k8s, mt_total); return; }
-    const float* src = gu + (size_t)j * 2 * f;
-    for (int k8 = threadIdx.x; k8 < k8s; k8 += blockDim.x) {
-        float y[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            float g = 0.f, u = 0.f;
-            for (int s = 0; s < n_partial; ++s) {
-                g += src[s * partial_stride + k8 * 8 + q];
-                u += src[s * partial_stride + f + k8 * 8 + q];
-            }
-            y[q] = g / (1.0f + expf(-g)) * u;
-        }
-        store_split(Apk, j, k8, mt_total, y);
-    }
-}
-
-void launch_swiglu_pack(const Dev& D, const float* gu, int n_partial, size_t partial_stride, u32x4* Apk,
-                        int rows_cap, int mt_total, hipStream_t s) {
-    (void)rows_cap;
-    swiglu_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, gu, n_partial, partial_stride, Apk, mt_total);
+    rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, gain, Apk, mt_total, gather, bcast);
 }
 
 // Top-1 confidence c = max_v softmax(l)_v = 1 / sum_v exp(l_v - max) and its token, in one
