@@ -200,6 +200,11 @@ int bb_profile_read(bb_ctx* ctx, bb_profile_entry* out_host, int max_entries, in
 int bb_debug_gemm(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, float* C_host,
                   int M, int N, int K, int split_k);
 
+/* Tuning knob: override the tile width (nt = 1: 128 columns, 2: 256; 0 = heuristic) and the
+ * split-K factor (0 = heuristic) of one GEMM kind (0 LM head, 1 O/down, 2 gate/up, 3 QKV) for
+ * panels of at most 128 rows.  Results are unchanged up to fp32 summation order. */
+int bb_debug_set_gemm_plan(bb_ctx* ctx, int kind, int nt, int split_k);
+
 #ifdef __cplusplus
 }
 #endif

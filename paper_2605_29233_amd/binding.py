@@ -63,7 +63,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -99,6 +99,7 @@ def load_library():
         lib.bb_get_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         lib.bb_read_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         lib.bb_synchronize.argtypes = [C.c_void_p]
+        lib.bb_debug_set_gemm_plan.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
         lib.bb_profile_enable.argtypes = [C.c_void_p, C.c_int]
         lib.bb_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]
         lib.bb_debug_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
@@ -242,6 +243,9 @@ class BlockBatch:
     # -- inspection ---------------------------------------------------------------------------
     def synchronize(self):
         self._chk(self.lib.bb_synchronize(self._ctx), "bb_synchronize")
+
+    def set_gemm_plan(self, kind, nt, split_k):
+        self._chk(self.lib.bb_debug_set_gemm_plan(self._ctx, kind, nt, split_k), "bb_debug_set_gemm_plan")
 
     def profile_enable(self, on=True):
         self._chk(self.lib.bb_profile_enable(self._ctx, int(on)), "bb_profile_enable")

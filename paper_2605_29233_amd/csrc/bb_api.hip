@@ -29,6 +29,7 @@ struct bb_ctx {
     u32x4 *Apk, *Apk2; half_t* Q; char* stage;     // Apk2: SwiGLU output panel (written while Apk is still being read)
     size_t qkv_elems, part_elems, gu_elems, stage_bytes, dbg_bytes;
     int refresh_rows_cap, ngu;
+    int force_nt[4], force_split[4];   // tuning overrides per epilogue kind (0 = heuristic)
     std::vector<HostReq> reqs;
     char* d_stats;                      // device staging for stats copies
     std::string err;
@@ -75,11 +76,13 @@ struct Bump {
 static size_t buf_elems(int rows_cap, int N, int K) {
     size_t best = 0;
     for (int rows = 32; rows <= (rows_cap + 31) / 32 * 32; rows += 32) {
-        GemmPlan p = gemm_plan(rows, N, K, 0);
+        GemmPlan p = gemm_plan(rows, N, K, 0, 0);
         size_t e = (size_t)p.split_k * rows * N;
         if (e > best) best = e;
     }
-    return best;
+    // room for the largest split a tuning override may ask for on a skinny panel
+    size_t tune = (size_t)BB_MAX_SPLITK * std::min((rows_cap + 31) / 32 * 32, 128) * N;
+    return std::max(best, tune);
 }
 
 static int check_cfg(const bb_model_cfg* m, const bb_limits* l, std::string* why) {
@@ -89,6 +92,7 @@ static int check_cfg(const bb_model_cfg* m, const bb_limits* l, std::string* why
     if (m->n_q_heads % m->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
     if (m->d_model % 16 || m->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
     if (m->d_model % 32 || (2 * m->d_ffn) % 32 || m->vocab % 32) return bad("projection row counts must be multiples of 32");
+    if ((m->n_q_heads * m->head_dim) % 128 || (m->n_kv_heads * m->head_dim) % 128) return bad("q and kv widths must be multiples of 128");
     if (m->mask_id < 0 || m->mask_id >= m->vocab) return bad("mask_id out of range");
     if (l->max_branches < 1 || l->max_branches > BB_MAX_BRANCHES) return bad("max_branches out of range");
     if (l->max_requests < 1 || l->max_requests * l->max_branches > 256) return bad("max_requests * max_branches must be <= 256");
@@ -137,14 +141,13 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.out_pred = b.take<int>(lm_pad); D.out_conf = b.take<float>(lm_pad); D.out_lse = b.take<float>(lm_pad);
     D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
     D.req_list = b.take<int>(l.max_requests);
-    D.tile_counters = b.take<int>(BB_TILE_COUNTERS);
     c->d_stats = b.take<char>(sizeof(ReqHeader) + sizeof(bb_branch_state) * BB_MAX_BRANCHES);
     D.Kc = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
     D.Vt = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
     size_t state_end = align_up(b.off, 256);
     // activations
     const int kmax = std::max(std::max(m.d_model, m.d_ffn), nq);
-    c->ngu = (m.d_ffn + 127) / 128 * 256;          // fused gate/up rows: 128 gate + 128 up per 256-column tile
+    c->ngu = (m.d_ffn + 63) / 64 * 128;            // fused gate/up rows: 64 gate rows, then the 64 up rows of the same features
     c->h = b.take<float>((size_t)rows_pad * m.d_model);
     c->Apk = b.take<u32x4>((size_t)rows_pad * kmax / 8 * BB_SPLIT);
     c->Apk2 = b.take<u32x4>((size_t)rows_pad * m.d_ffn / 8 * BB_SPLIT);
@@ -211,7 +214,7 @@ extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decod
     size_t zero_bytes = (char*)c->emb - c->ws;
     hipError_t e = hipMemsetAsync(c->ws, 0, zero_bytes, c->stream);
     if (e != hipSuccess) { delete c; return BB_EHIP; }
-    if (model->d_ffn % 128)                              // padded gate/up rows must be finite
+    if (model->d_ffn % 64)                              // padded gate/up rows must be finite
         for (auto& L : c->layers)
             if (e == hipSuccess) e = hipMemsetAsync(L.wgu, 0, (size_t)c->ngu * model->d_model * 2, c->stream);
     if (e != hipSuccess) { delete c; return BB_EHIP; }
@@ -298,7 +301,7 @@ static int load_one(bb_ctx* c, const bb_tensor& t) {
             case 7: ok = expect(d, nq); if (ok) launch_tile_weights(src, d, nq, L.wo, 0, 0, c->stream); break;
             case 8: ok = t.rows * t.cols == d; if (ok) widen(L.g_ffn, d); break;
             case 9: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 0, 1, c->stream); break;
-            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 128, 1, c->stream); break;
+            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 64, 1, c->stream); break;
             case 11: ok = expect(d, f); if (ok) launch_tile_weights(src, d, f, L.wdown, 0, 0, c->stream); break;
         }
     } else return fail(c, BB_EINVAL, "unknown tensor " + name);
@@ -386,31 +389,37 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const int d = m.d_model, nq = m.n_q_heads * m.head_dim, f = m.d_ffn, nqkv = D.nqkv, ngu = c->ngu;
     const int mt = (rows_cap + 31) / 32, rows_pad = mt * 32;
     const int gk = rows_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
-    auto gemm = [&](int epi, EpiArgs E, const u32x4* W, const u32x4* A, float* P, int N, int K, int rows, int mtt, int klass, int force) {
-        GemmPlan p = gemm_plan(rows, N, K, force);
-        E.P = P; E.ldp = N; E.split_stride = (size_t)mtt * 32 * N; E.counters = D.tile_counters;
+    // kind: 0 LM head, 1 O/down, 2 gate/up, 3 QKV (index of the tuning overrides)
+    auto gemm = [&](int kind, const u32x4* W, const u32x4* A, float* P, int N, int K, int rows, int mtt, int klass) {
+        GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, c->force_nt[kind]);
+        if (c->force_split[kind] > 0 && kind != 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
         PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-        launch_gemm(D, epi, E, W, A, mtt, N, K, p, s);
+        launch_gemm(W, A, P, mtt, N, K, p, s);
+        return p.split_k;
     };
-    EpiArgs E0; memset(&E0, 0, sizeof(E0));
-    E0.m_count = D.counts; E0.h = c->h; E0.ldh = d; E0.Apk = c->Apk2; E0.mt_total = mt; E0.f = f; E0.Q = c->Q;
     { PROF(BB_K_GLUE, 0, 0); launch_embed(D, c->emb, c->h, rows_cap, s); }
+    int s_down = 0;
+    const size_t pstride = (size_t)rows_pad * d;
     for (int li = 0; li < m.n_layers; ++li) {
         const LayerW& W = c->layers[li];
-        EpiArgs E = E0; E.layer = li; E.bias = m.qkv_bias ? W.bqkv : nullptr;
-        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, W.g_attn, c->Apk, mt, 0, 0, s); }
-        gemm(EPI_QKV, E, W.wqkv, c->Apk, c->qkv, nqkv, d, rows_cap, mt, gk, 0);
+        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, 0, 0, s); }
+        const int s_qkv = gemm(3, W.wqkv, c->Apk, c->qkv, nqkv, d, rows_cap, mt, gk);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_qkv_epilogue(D, c->qkv, s_qkv, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s); }
         if (mode == 2 && li == m.n_layers - 1) break;
         { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, s); }
-        gemm(EPI_RESID, E, W.wo, c->Apk, c->part, d, nq, rows_cap, mt, gk, 0);
-        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, W.g_ffn, c->Apk, mt, 0, 0, s); }
-        gemm(EPI_SWIGLU, E, W.wgu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, 0);
-        gemm(EPI_RESID, E, W.wdown, c->Apk2, c->part, d, f, rows_cap, mt, gk, 0);
+        const int s_o = gemm(1, W.wo, c->Apk, c->part, d, nq, rows_cap, mt, gk);
+        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, s); }
+        const int s_gu = gemm(2, W.wgu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_swiglu_epilogue(D, c->gu, s_gu, (size_t)rows_pad * ngu, ngu, c->Apk2, rows_cap, mt, s); }
+        s_down = gemm(1, W.wdown, c->Apk2, c->part, d, f, rows_cap, mt, gk);
     }
     if (mode != 2) {
         const int mt_lm = (lm_cap + 31) / 32;
-        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->g_final, c->Apk, mt_lm, 1, mode == 1, s); }
-        gemm(EPI_NONE, E0, c->lm, c->Apk, c->logits, m.vocab, d, lm_cap, mt_lm, lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE, 1);
+        { PROF(BB_K_GLUE, 0, 0);
+          launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, c->g_final, c->Apk, mt_lm, 1, mode == 1, s); }
+        gemm(0, c->lm, c->Apk, c->logits, m.vocab, d, lm_cap, mt_lm, lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE);
         { PROF(BB_K_GLUE, 0, 0); launch_vocab_reduce(D, c->logits, lm_cap, mode == 1, s); }
     }
     c->last_forward_rows = rows_cap; c->last_lm_cap = lm_cap;
@@ -491,6 +500,12 @@ extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stat
 // ---- inspection and teacher forcing ---------------------------------------------------------------------
 static int check_one(bb_ctx* c, int id) {
     if (!c || id < 0 || id >= c->lim.max_requests || !c->reqs[id].in_use) return BB_EINVAL;
+    return BB_OK;
+}
+
+extern "C" int bb_debug_set_gemm_plan(bb_ctx* c, int kind, int nt, int split_k) {
+    if (!c || kind < 0 || kind > 3 || nt < 0 || nt > 2 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
+    c->force_nt[kind] = nt; c->force_split[kind] = split_k;
     return BB_OK;
 }
 
@@ -587,7 +602,7 @@ extern "C" int bb_get_kv(bb_ctx* c, int id, int branch, int layer, float* K, flo
 extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
     if (!c || !A || !W || !C || M < 1 || N < 32 || K < 16 || N % 32 || K % 16 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     const int mt = (M + 31) / 32, rows_pad = mt * 32;
-    GemmPlan p = gemm_plan(M, N, K, split_k);
+    GemmPlan p = gemm_plan(M, N, K, split_k, 0);
     // carve private buffers out of the activation region [h, emb): nothing else runs meanwhile
     Bump b{(char*)c->h, 0};
     float* dA = b.take<float>((size_t)M * K);
@@ -601,9 +616,7 @@ extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float
     HIPCHK(c, hipMemcpyAsync(dW, W, (size_t)N * K * 2, hipMemcpyHostToDevice, c->stream));
     launch_tile_weights(dW, N, K, dWt, 0, 0, c->stream);
     launch_pack_rows(dA, M, K, dAp, mt, c->stream);
-    EpiArgs E; memset(&E, 0, sizeof(E));
-    E.P = dC; E.ldp = N; E.split_stride = (size_t)rows_pad * N; E.counters = c->D.tile_counters; E.m_count = c->D.counts;
-    launch_gemm(c->D, EPI_NONE, E, dWt, dAp, mt, N, K, p, c->stream);
+    launch_gemm(dWt, dAp, dC, mt, N, K, p, c->stream);
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipStreamSynchronize(c->stream));
     std::vector<float> tmp(c_elems);

@@ -11,7 +11,6 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define BB_PAGE 64              // tokens per KV page = keys per attention tile
 #define BB_SPLIT 2              // bf16 terms per activation (hi + lo) fed to the MFMA GEMMs
 #define BB_MAX_SPLITK 16
-#define BB_TILE_COUNTERS 4096
 
 // ---- device-resident request state ------------------------------------------------------
 struct ReqHeader {
@@ -59,7 +58,6 @@ struct Dev {
     int* out_pred; float* out_conf; float* out_lse;   // [lm_cap]
     PageCopy* copies;           // [max_req*max_br*n_pages]
     int* req_list;              // [max_req] request slots of the current call
-    int* tile_counters;         // [BB_TILE_COUNTERS] split-K arrival counters, zero between launches
 };
 
 static inline __host__ __device__ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -90,31 +88,22 @@ static inline __host__ __device__ float bf16_to_f32(uint16_t b) {
 }
 
 // ---- kernel launchers (each enqueues on `s`) -----------------------------------------------------
-struct GemmPlan { int split_k; int chunks_per_split; };
-GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split);
-enum { EPI_NONE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_QKV = 3 };
-
-struct EpiArgs {
-    float* P; size_t split_stride; int ldp, n_split;
-    int* counters;
-    const int* m_count;         // device: number of valid activation rows
-    // EPI_RESID: h[m][n] += sum
-    float* h; int ldh;
-    // EPI_SWIGLU: act = SiLU(gate) * up -> packed hi/lo panel with K = f
-    u32x4* Apk; int mt_total, f;
-    // EPI_QKV: bias, RoPE, q -> Q (two fp16 terms), k,v -> cache rows
-    const float* bias; half_t* Q; int layer;
-};
-
-void launch_gemm(const Dev& D, int epi, const EpiArgs& E, const u32x4* Wt, const u32x4* Apk, int mt_total, int N, int K,
-                 GemmPlan plan, hipStream_t s);
+struct GemmPlan { int split_k; int chunks_per_split; int nt; };
+GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt);
+void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s);
 void launch_tile_weights(const uint16_t* src, int rows, int K, u32x4* dst, int dst_row0, int interleave, hipStream_t s);
 void launch_pack_rows(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);
 
 void launch_embed(const Dev& D, const uint16_t* emb, float* h, int rows_cap, hipStream_t s);
-// out = packed rmsnorm(h) * gain.  gather != 0: rows are the masked (LM-head) rows.
-void launch_rmsnorm_pack(const Dev& D, const float* h, const float* gain, u32x4* Apk, int mt_total, int gather, int bcast,
-                         hipStream_t s);
+// h += sum of split-K partials; out = packed rmsnorm(h) * gain.  gather != 0: rows are the masked (LM-head) rows.
+void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
+                         const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, hipStream_t s);
+// q,k,v = sum of partials + bias; RoPE; q -> Q, k,v -> cache rows (two fp16 terms each)
+void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t partial_stride, const float* bias,
+                         half_t* Q, int layer, int rows_cap, hipStream_t s);
+// act = SiLU(gate) * up from the fused (64-row interleaved) gate/up projection -> packed panel with K = f
+void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
+                            int rows_cap, int mt_total, hipStream_t s);
 void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int mt_total, int max_seg_rows,
                       int seg_base, int n_segs, hipStream_t s);
 void launch_vocab_reduce(const Dev& D, const float* logits, int lm_cap, int bcast, hipStream_t s);

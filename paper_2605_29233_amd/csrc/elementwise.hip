@@ -1,6 +1,6 @@
-// Memory-bound glue kernels of the forward: embedding gather, RMSNorm with packing into MFMA
-// fragments, and the online-softmax vocabulary reduction.  (Residual adds, SwiGLU, RoPE and
-// the cache write live in the GEMM epilogues.)
+// Memory-bound glue kernels of the forward: embedding gather, the consumers of the GEMMs'
+// split-K partial results (residual add + RMSNorm + packing into MFMA fragments, bias + RoPE +
+// KV-cache write, SwiGLU), and the online-softmax vocabulary reduction.
 #include "bb_internal.h"
 
 static __device__ __forceinline__ float wg_sum(float v, float* sh) {
@@ -48,25 +48,48 @@ void launch_embed(const Dev& D, const uint16_t* emb, float* h, int rows_cap, hip
     embed_kernel<<<rows_cap, 256, 0, s>>>(D, emb, h);
 }
 
+// Sum of split-K partial results in split order; all loads of a batch of four are issued
+// before the first add so several are in flight per thread.
+static __device__ __forceinline__ float4 part_sum4(const float* __restrict__ P, int n_split, size_t stride, size_t off) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < n_split; s += 4) {
+        float4 p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            p[u] = s + u < n_split ? *reinterpret_cast<const float4*>(&P[(s + u) * stride + off]) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w; }
+    }
+    return v;
+}
+
 // One workgroup per destination row j of the packed panel.  Source row r = j, or the j-th
-// masked row when gather != 0 (LM-head panel).  y = h / sqrt(mean(h^2) + eps) * gain.
+// masked row when gather != 0 (LM-head panel).  h[r] += sum_s partial[s][r] first (the residual
+// add of the preceding O / down projection), then y = h / sqrt(mean(h^2) + eps) * gain.
 // In gather mode y is also stored as the branch's probability-map entry for that position
 // (P_k(i, v) = exp(y . W_v - lse) is evaluated on demand by the merge), for every branch of
 // the request when bcast != 0 (initial forward: all rows are identical).
-__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, const float* __restrict__ h, const float* __restrict__ gain,
-                                                           u32x4* __restrict__ Apk, int mt_total, int gather, int bcast) {
+__global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restrict__ h, const float* __restrict__ partial,
+                                                           int n_partial, size_t partial_stride,
+                                                           const float* __restrict__ gain, u32x4* __restrict__ Apk,
+                                                           int mt_total, int gather, int bcast) {
     __shared__ float sh[4];
     const int j = blockIdx.x, d = D.d, k8s = d >> 3;
     const int count = gather ? D.counts[1] : D.counts[0];
     if (j >= count) { zero_packed_row(Apk, j, k8s, mt_total); return; }
     const int r = gather ? D.lm_row[j] : j;
-    const float* hr = h + (size_t)r * d;
+    float* hr = h + (size_t)r * d;
     float ss = 0.f;
     for (int k4 = threadIdx.x; k4 < (d >> 2); k4 += blockDim.x) {
-        const float4 v = reinterpret_cast<const float4*>(hr)[k4];
+        float4 v = reinterpret_cast<float4*>(hr)[k4];
+        if (n_partial) {
+            const float4 p = part_sum4(partial, n_partial, partial_stride, (size_t)r * d + k4 * 4);
+            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+            reinterpret_cast<float4*>(hr)[k4] = v;
+        }
         ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
-    ss = wg_sum(ss, sh);
+    ss = wg_sum(ss, sh);            // also orders the writes to hr before the reads below
     const float inv = 1.0f / sqrtf(ss / (float)d + D.rms_eps);
     int gbr = 0, nb = 1; size_t mrow = 0;
     if (gather) {
@@ -90,9 +113,124 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, const float* _
     }
 }
 
-void launch_rmsnorm_pack(const Dev& D, const float* h, const float* gain, u32x4* Apk, int mt_total, int gather, int bcast,
-                         hipStream_t s) {
-    rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, gain, Apk, mt_total, gather, bcast);
+void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
+                         const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, hipStream_t s) {
+    rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, gather, bcast);
+}
+
+static __device__ __forceinline__ void put2(half_t* hi_p, half_t* lo_p, float y) {
+    const half_t hi = (half_t)y;
+    *hi_p = hi;
+    *lo_p = (half_t)(y - (float)hi);
+}
+
+// QKV epilogue.  One workgroup = 16 packed rows x 128 columns (whole heads) of the fused q|k|v
+// projection: sum the split-K partials (+ bias); q and k heads are rotated by the row's
+// absolute position (pairs (j, j + hd/2), angles from a host-computed table) and stored as two
+// fp16 terms (q for the attention kernel, k into the row's cache page); v heads are transposed
+// through LDS so that the stores into the transposed cache run along the token axis.
+__global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* __restrict__ qkv, int n_partial,
+                                                           size_t partial_stride, const float* __restrict__ bias,
+                                                           half_t* __restrict__ Q, int layer) {
+    __shared__ float tile[128][17];
+    const int m0 = blockIdx.x * 16, c0 = blockIdx.y * 128, t = threadIdx.x;
+    const int count = D.counts[0];
+    if (m0 >= count) return;
+    const int hd = D.hd, half = hd >> 1, nq = D.hq * hd, nk = D.hkv * hd;
+    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
+    if (c0 < nq + nk) {
+        // 16 rows x (128 / hd heads) x hd/8 groups of 4 pairs = 256 work items
+        const int per_row = 16, r = t / per_row, m = m0 + r;
+        if (m >= count) return;
+        const int hh = (t % per_row) / (half >> 2), j = ((t % per_row) % (half >> 2)) * 4;
+        const int ch = c0 + hh * hd;                   // first column of this head
+        const size_t off = (size_t)m * D.nqkv + ch + j;
+        float4 x1 = part_sum4(qkv, n_partial, partial_stride, off);
+        float4 x2 = part_sum4(qkv, n_partial, partial_stride, off + half);
+        if (bias) {
+            const float4 b1 = *reinterpret_cast<const float4*>(&bias[ch + j]);
+            const float4 b2 = *reinterpret_cast<const float4*>(&bias[ch + j + half]);
+            x1.x += b1.x; x1.y += b1.y; x1.z += b1.z; x1.w += b1.w;
+            x2.x += b2.x; x2.y += b2.y; x2.z += b2.z; x2.w += b2.w;
+        }
+        const int pos = D.row_pos[m];
+        const float4 c = *reinterpret_cast<const float4*>(&D.rope_cos[(size_t)pos * half + j]);
+        const float4 sn = *reinterpret_cast<const float4*>(&D.rope_sin[(size_t)pos * half + j]);
+        const float a1[4] = {x1.x, x1.y, x1.z, x1.w}, a2[4] = {x2.x, x2.y, x2.z, x2.w};
+        const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
+        half_t* dst = ch < nq ? Q + ((size_t)m * D.hq + ch / hd) * 2 * hd
+                              : D.Kc + ((((size_t)layer * phys_rows + D.row_phys[m]) * D.lpad + pos) * D.hkv + (ch - nq) / hd) * 2 * hd;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            put2(dst + j + e, dst + hd + j + e, a1[e] * cc[e] - a2[e] * ss[e]);
+            put2(dst + j + e + half, dst + hd + j + e + half, a2[e] * cc[e] + a1[e] * ss[e]);
+        }
+        return;
+    }
+    // v columns
+    {
+        const int r = t / 16, cg = (t % 16) * 8, m = m0 + r;
+        if (m < count) {
+            const size_t off = (size_t)m * D.nqkv + c0 + cg;
+            float4 v0 = part_sum4(qkv, n_partial, partial_stride, off);
+            float4 v1 = part_sum4(qkv, n_partial, partial_stride, off + 4);
+            if (bias) {
+                const float4 b0 = *reinterpret_cast<const float4*>(&bias[c0 + cg]);
+                const float4 b1 = *reinterpret_cast<const float4*>(&bias[c0 + cg + 4]);
+                v0.x += b0.x; v0.y += b0.y; v0.z += b0.z; v0.w += b0.w;
+                v1.x += b1.x; v1.y += b1.y; v1.z += b1.z; v1.w += b1.w;
+            }
+            tile[cg + 0][r] = v0.x; tile[cg + 1][r] = v0.y; tile[cg + 2][r] = v0.z; tile[cg + 3][r] = v0.w;
+            tile[cg + 4][r] = v1.x; tile[cg + 5][r] = v1.y; tile[cg + 6][r] = v1.z; tile[cg + 7][r] = v1.w;
+        }
+    }
+    __syncthreads();
+    for (int it = t; it < 128 * 16; it += 256) {
+        const int c = it / 16, r = it % 16, m = m0 + r;
+        if (m >= count) continue;
+        const int e = c0 + c - nq - nk, head = e / hd, dd = e % hd;
+        half_t* base = D.Vt + (((size_t)layer * phys_rows + D.row_phys[m]) * D.hkv + head) * 2 * hd * (size_t)D.lpad;
+        const int pos = D.row_pos[m];
+        put2(base + (size_t)dd * D.lpad + pos, base + (size_t)(hd + dd) * D.lpad + pos, tile[c][r]);
+    }
+}
+
+void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t partial_stride, const float* bias,
+                         half_t* Q, int layer, int rows_cap, hipStream_t s) {
+    dim3 grid((rows_cap + 15) / 16, D.nqkv / 128);
+    qkv_epilogue_kernel<<<grid, 256, 0, s>>>(D, qkv, n_partial, partial_stride, bias, Q, layer);
+}
+
+// act = SiLU(gate) * up.  The fused matrix alternates 64 gate rows with the 64 up rows of the
+// same features, so feature f has its gate in column (f / 64) * 128 + f % 64 and its up 64 further.
+__global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float* __restrict__ gu, int n_partial,
+                                                              size_t partial_stride, int ldp, u32x4* __restrict__ Apk,
+                                                              int mt_total) {
+    const int f8s = D.f >> 3;
+    const size_t it = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int m = (int)(it / f8s), f = (int)(it % f8s) * 8;
+    if (m >= mt_total * 32) return;
+    if (m >= D.counts[0]) {
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        Apk[packA_u4(m, f >> 3, mt_total, 0)] = z; Apk[packA_u4(m, f >> 3, mt_total, 1)] = z;
+        return;
+    }
+    const size_t off = (size_t)m * ldp + (f >> 6) * 128 + (f & 63);
+    const float4 g0 = part_sum4(gu, n_partial, partial_stride, off), g1 = part_sum4(gu, n_partial, partial_stride, off + 4);
+    const float4 u0 = part_sum4(gu, n_partial, partial_stride, off + 64), u1 = part_sum4(gu, n_partial, partial_stride, off + 68);
+    const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+    const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+    float y[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) y[q] = g[q] / (1.0f + expf(-g[q])) * u[q];
+    store_split(Apk, m, f >> 3, mt_total, y);
+}
+
+void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
+                            int rows_cap, int mt_total, hipStream_t s) {
+    (void)rows_cap;
+    const size_t items = (size_t)mt_total * 32 * (D.f >> 3);
+    swiglu_epilogue_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(D, gu, n_partial, partial_stride, ldp, Apk, mt_total);
 }
 
 // Top-1 confidence c = max_v softmax(l)_v = 1 / sum_v exp(l_v - max) and its token, in one
