@@ -90,7 +90,7 @@ static int check_cfg(const bb_model_cfg* m, const bb_limits* l, std::string* why
     if (!m || !l) return bad("null config");
     if (m->head_dim != 64 && m->head_dim != 128) return bad("head_dim must be 64 or 128");
     if (m->n_q_heads % m->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
-    if (m->d_model % 16 || m->d_ffn % 16) return bad("d_model and d_ffn must be multiples of 16");
+    if (m->d_model % 64 || m->d_ffn % 16) return bad("d_model must be a multiple of 64 and d_ffn of 16");
     if (m->d_model % 32 || (2 * m->d_ffn) % 32 || m->vocab % 32) return bad("projection row counts must be multiples of 32");
     if ((m->n_q_heads * m->head_dim) % 128 || (m->n_kv_heads * m->head_dim) % 128) return bad("q and kv widths must be multiples of 128");
     if (m->mask_id < 0 || m->mask_id >= m->vocab) return bad("mask_id out of range");
@@ -150,7 +150,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     c->ngu = (m.d_ffn + 63) / 64 * 128;            // fused gate/up rows: 64 gate rows, then the 64 up rows of the same features
     c->h = b.take<float>((size_t)rows_pad * m.d_model);
     c->Apk = b.take<u32x4>((size_t)rows_pad * kmax / 8 * BB_SPLIT);
-    c->Apk2 = b.take<u32x4>((size_t)rows_pad * m.d_ffn / 8 * BB_SPLIT);
+    c->Apk2 = b.take<u32x4>((size_t)rows_pad * ((m.d_ffn + 63) / 64 * 64) / 8 * BB_SPLIT);
     c->Q = b.take<half_t>((size_t)rows_pad * nq * 2);
     c->qkv_elems = buf_elems(rows_cap, nqkv, m.d_model);
     c->part_elems = std::max(buf_elems(rows_cap, m.d_model, nq), buf_elems(rows_cap, m.d_model, m.d_ffn));
@@ -175,7 +175,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
         L.wqkv = b.take<u32x4>((size_t)nqkv * m.d_model / 8);
         L.wo = b.take<u32x4>((size_t)m.d_model * nq / 8);
         L.wgu = b.take<u32x4>((size_t)c->ngu * m.d_model / 8);
-        L.wdown = b.take<u32x4>((size_t)m.d_model * m.d_ffn / 8);
+        L.wdown = b.take<u32x4>((size_t)m.d_model * ((m.d_ffn + 63) / 64 * 64) / 8);
         L.g_attn = b.take<float>(m.d_model); L.g_ffn = b.take<float>(m.d_model);
         L.bqkv = b.take<float>(nqkv);
     }
@@ -607,13 +607,15 @@ extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float
     Bump b{(char*)c->h, 0};
     float* dA = b.take<float>((size_t)M * K);
     uint16_t* dW = b.take<uint16_t>((size_t)N * K);
-    u32x4* dWt = b.take<u32x4>((size_t)N * K / 8);
-    u32x4* dAp = b.take<u32x4>((size_t)rows_pad * K / 8 * BB_SPLIT);
+    const int Kp = (K + 63) / 64 * 64;
+    u32x4* dWt = b.take<u32x4>((size_t)N * Kp / 8);
+    u32x4* dAp = b.take<u32x4>((size_t)rows_pad * Kp / 8 * BB_SPLIT);
     const size_t c_elems = (size_t)p.split_k * rows_pad * N;
     float* dC = b.take<float>(c_elems);
     if (b.off > (size_t)((char*)c->emb - (char*)c->h)) return fail(c, BB_ENOMEM, "debug gemm does not fit the activation region");
     HIPCHK(c, hipMemcpyAsync(dA, A, (size_t)M * K * 4, hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, hipMemcpyAsync(dW, W, (size_t)N * K * 2, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipMemsetAsync(dWt, 0, (size_t)N * Kp * 2, c->stream));
     launch_tile_weights(dW, N, K, dWt, 0, 0, c->stream);
     launch_pack_rows(dA, M, K, dAp, mt, c->stream);
     launch_gemm(dWt, dAp, dC, mt, N, K, p, c->stream);

@@ -206,11 +206,11 @@ void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t p
 __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float* __restrict__ gu, int n_partial,
                                                               size_t partial_stride, int ldp, u32x4* __restrict__ Apk,
                                                               int mt_total) {
-    const int f8s = D.f >> 3;
+    const int f8s = (D.f + 63) / 64 * 8;                   // the panel's K is padded to whole chunks of 64 with zeros
     const size_t it = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int m = (int)(it / f8s), f = (int)(it % f8s) * 8;
     if (m >= mt_total * 32) return;
-    if (m >= D.counts[0]) {
+    if (m >= D.counts[0] || f >= D.f) {
         const u32x4 z = {0u, 0u, 0u, 0u};
         Apk[packA_u4(m, f >> 3, mt_total, 0)] = z; Apk[packA_u4(m, f >> 3, mt_total, 1)] = z;
         return;
@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float
 void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
                             int rows_cap, int mt_total, hipStream_t s) {
     (void)rows_cap;
-    const size_t items = (size_t)mt_total * 32 * (D.f >> 3);
+    const size_t items = (size_t)mt_total * 32 * ((D.f + 63) / 64 * 8);
     swiglu_epilogue_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(D, gu, n_partial, partial_stride, ldp, Apk, mt_total);
 }
 

@@ -14,81 +14,85 @@
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-#define KC 4        // k-steps (of 16) per LDS chunk
+#define KC 4        // k-steps (of 16) per staged chunk
 #define MT 4        // m-tiles (of 32 rows) per workgroup
-#define CHUNK_U4 (KC * MT * BB_SPLIT * 64)      // u32x4 per staged chunk (2048 = 32 KiB)
+#define DW 3        // weight chunks per wave in the register ring (two in flight ahead of the MFMAs)
+#define CHUNK_U4 (KC * MT * BB_SPLIT * 64)      // uint4 per staged activation chunk (2048 = 32 KiB)
+#define A_PER_THREAD (CHUNK_U4 / 256)
 
 static __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
     return *reinterpret_cast<const bf16x8*>(&v);
 }
 
-template <int NT>
-static __device__ __forceinline__ void load_w(u32x4 (&w)[KC][NT], const u32x4* __restrict__ Wt, const int (&nt)[NT],
-                                              int ksteps, int ks0, int lane) {
-#pragma unroll
-    for (int t = 0; t < NT; ++t)
-#pragma unroll
-        for (int k = 0; k < KC; ++k) {
-            int ks = ks0 + k < ksteps ? ks0 + k : ksteps - 1;      // clamped; the product is skipped later
-            w[k][t] = __builtin_nontemporal_load(&Wt[((size_t)nt[t] * ksteps + ks) * 64 + lane]);
-        }
-}
-
-static __device__ __forceinline__ void load_a(u32x4 (&a)[CHUNK_U4 / 256], const u32x4* __restrict__ Apk, int mt_total,
-                                              int mt0, int mt_cnt, int ksteps, int ks0) {
-#pragma unroll
-    for (int i = 0; i < CHUNK_U4 / 256; ++i) {
-        int idx = i * 256 + threadIdx.x;
-        int k = idx / (MT * BB_SPLIT * 64), rem = idx % (MT * BB_SPLIT * 64);
-        int mt = rem / (BB_SPLIT * 64), tl = rem % (BB_SPLIT * 64);
-        u32x4 v = u32x4{0u, 0u, 0u, 0u};
-        if (mt < mt_cnt && ks0 + k < ksteps)
-            v = Apk[((size_t)(ks0 + k) * mt_total + mt0 + mt) * (BB_SPLIT * 64) + tl];
-        a[i] = v;
-    }
-}
-
-template <int NT>
-static __device__ __forceinline__ void compute_chunk(f32x16 (&acc)[NT][MT], const u32x4 (&w)[KC][NT], const u32x4* lds,
-                                                     int mt_cnt, int kvalid, int lane) {
-#pragma unroll
-    for (int k = 0; k < KC; ++k) {
-        if (k < kvalid) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                if (mt < mt_cnt) {
-#pragma unroll
-                    for (int term = 0; term < BB_SPLIT; ++term) {
-                        u32x4 b = lds[((k * MT + mt) * BB_SPLIT + term) * 64 + lane];
-#pragma unroll
-                        for (int t = 0; t < NT; ++t)
-                            acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w[k][t]), as_bf16x8(b),
-                                                                                acc[t][mt], 0, 0, 0);
-                    }
-                }
-            }
-        }
-    }
-}
+// sched_group_barrier masks
+#define SG_MFMA 0x008
+#define SG_VMEM 0x020
+#define SG_DSR 0x100
+#define SG_DSW 0x200
 
 // P[split][m][n] (fp32, leading dimension ldp) = this workgroup's share of the k range.
+//
+// One workgroup = 4 waves = one wave per SIMD; wave w owns NT weight tiles (32 rows each) and all
+// four waves share the activation chunk in LDS, so the tile is 128 rows x (128 * NT) columns.
+// Per chunk of 64 k a wave issues 16 * NT * 2 MFMAs, 32 LDS fragment reads, its 8 LDS writes of the
+// next activation chunk and 16 global loads; with a single wave per SIMD nothing hides a stall,
+// so the chunk is a software pipeline with every stream interleaved between the MFMAs:
+//   k-step 0: MFMAs | LDS reads of step 1 | LDS writes of chunk c+1's activations (loaded during c-1)
+//   k-step 1: MFMAs | LDS reads of step 2 | global loads of chunk c+2's activations     -> barrier
+//   k-step 2: MFMAs | LDS reads of step 3 | global loads of half of chunk c+2's weights
+//   k-step 3: MFMAs | LDS reads of step 0 of chunk c+1 | the other half
+// Activations rotate through three LDS stages, weights through three register slots.  All loads
+// are unpredicated (indices clamped, K padded with zeros to whole chunks) so the loop body is one
+// straight block per chunk and the compiler's wait counts are exact.
 template <int NT>
-__global__ __launch_bounds__(256) void gemm_kernel(const u32x4* __restrict__ Wt, const u32x4* __restrict__ Apk,
-                                                   float* __restrict__ P, size_t split_stride, int ldp, int mt_total,
-                                                   int n_tiles, int ksteps, int chunks_per_split) {
-    __shared__ u32x4 lds[2][CHUNK_U4];
+__global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ Wt, const u32x4* __restrict__ Apk,
+                                                      float* __restrict__ P, size_t split_stride, int ldp, int mt_total,
+                                                      int n_tiles, int ksteps, int chunks_per_split) {
+    __shared__ u32x4 lds[3][CHUNK_U4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int mt0 = blockIdx.y * MT;
     const int mt_cnt = min(MT, mt_total - mt0);
-    const int total_chunks = (ksteps + KC - 1) / KC;
+    const int total_chunks = ksteps / KC;
     const int c0 = blockIdx.z * chunks_per_split;
     const int c1 = min(c0 + chunks_per_split, total_chunks);
-    int nt[NT];
+    if (c0 >= c1) return;
+
+    // weight stream: one pointer per tile, advanced by a chunk (KC fragments of 64 lanes) at a time
+    const u32x4* wbase[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        int x = (blockIdx.x * 4 + wave) * NT + t;
-        nt[t] = x < n_tiles ? x : n_tiles - 1;          // clamped loads; stores are guarded
+        const int x = min((int)(blockIdx.x * 4 + wave) * NT + t, n_tiles - 1);      // clamped loads; stores are guarded
+        wbase[t] = Wt + (size_t)x * ksteps * 64 + lane;
     }
+    // activation stream: per-thread offsets inside a chunk (missing m-tiles read a valid one)
+    int aoff[A_PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < A_PER_THREAD; ++i) {
+        const int idx = i * 256 + threadIdx.x;
+        const int k = idx / (MT * BB_SPLIT * 64), rem = idx % (MT * BB_SPLIT * 64);
+        aoff[i] = (k * mt_total + min(rem / (BB_SPLIT * 64), mt_cnt - 1)) * (BB_SPLIT * 64) + rem % (BB_SPLIT * 64);
+    }
+    const u32x4* abase = Apk + (size_t)mt0 * (BB_SPLIT * 64);
+    const size_t a_chunk = (size_t)KC * mt_total * (BB_SPLIT * 64);
+    auto load_a = [&](u32x4 (&a)[A_PER_THREAD], int c) {
+        const u32x4* p = abase + (size_t)min(c, c1 - 1) * a_chunk;
+#pragma unroll
+        for (int i = 0; i < A_PER_THREAD; ++i) a[i] = p[aoff[i]];
+    };
+    auto load_w = [&](u32x4 (&w)[KC][NT], int c, int k_lo, int k_hi) {
+        const size_t off = (size_t)min(c, c1 - 1) * (KC * 64);
+#pragma unroll
+        for (int k = k_lo; k < k_hi; ++k)
+#pragma unroll
+            for (int t = 0; t < NT; ++t) w[k][t] = __builtin_nontemporal_load(wbase[t] + off + k * 64);
+    };
+    auto read_b = [&](u32x4 (&b)[MT][BB_SPLIT], int stage, int k) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int term = 0; term < BB_SPLIT; ++term) b[mt][term] = lds[stage][((k * MT + mt) * BB_SPLIT + term) * 64 + lane];
+    };
+
     f32x16 acc[NT][MT];
 #pragma unroll
     for (int t = 0; t < NT; ++t)
@@ -96,41 +100,76 @@ __global__ __launch_bounds__(256) void gemm_kernel(const u32x4* __restrict__ Wt,
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[t][mt][r] = 0.f;
+    auto mfmas = [&](const u32x4 (&w)[NT], const u32x4 (&b)[MT][BB_SPLIT]) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int term = 0; term < BB_SPLIT; ++term)
+#pragma unroll
+                for (int t = 0; t < NT; ++t)
+                    acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(w[t]), as_bf16x8(b[mt][term]), acc[t][mt], 0, 0, 0);
+    };
 
-    u32x4 w0[KC][NT], w1[KC][NT], a[CHUNK_U4 / 256];
-    if (c0 < c1) {
-        load_a(a, Apk, mt_total, mt0, mt_cnt, ksteps, c0 * KC);
-        load_w<NT>(w0, Wt, nt, ksteps, c0 * KC, lane);
+    u32x4 w[DW][KC][NT], a[A_PER_THREAD], b[2][MT][BB_SPLIT];
+    // prologue: chunk c0 staged, chunk c0+1 in registers, weights of c0 and c0+1 in flight
+    load_a(a, c0);
+    load_w(w[0], c0, 0, KC);
+    load_w(w[1], c0 + 1, 0, KC);
 #pragma unroll
-        for (int i = 0; i < CHUNK_U4 / 256; ++i) lds[0][i * 256 + threadIdx.x] = a[i];
-    }
+    for (int i = 0; i < A_PER_THREAD; ++i) lds[0][i * 256 + threadIdx.x] = a[i];
+    load_a(a, c0 + 1);
     __syncthreads();
-    for (int c = c0; c < c1; c += 2) {
-        // even chunk: data in lds[0] / w0, prefetch into lds[1] / w1
-        bool more = c + 1 < c1;
-        if (more) {
-            load_a(a, Apk, mt_total, mt0, mt_cnt, ksteps, (c + 1) * KC);
-            load_w<NT>(w1, Wt, nt, ksteps, (c + 1) * KC, lane);
-        }
-        compute_chunk<NT>(acc, w0, lds[0], mt_cnt, min(KC, ksteps - c * KC), lane);
-        if (more) {
+    read_b(b[0], 0, 0);
+
+    for (int cb = c0; cb < c1; cb += DW) {
 #pragma unroll
-            for (int i = 0; i < CHUNK_U4 / 256; ++i) lds[1][i * 256 + threadIdx.x] = a[i];
-        }
-        __syncthreads();
-        if (!more) break;
-        // odd chunk: data in lds[1] / w1, prefetch into lds[0] / w0
-        more = c + 2 < c1;
-        if (more) {
-            load_a(a, Apk, mt_total, mt0, mt_cnt, ksteps, (c + 2) * KC);
-            load_w<NT>(w0, Wt, nt, ksteps, (c + 2) * KC, lane);
-        }
-        compute_chunk<NT>(acc, w1, lds[1], mt_cnt, min(KC, ksteps - (c + 1) * KC), lane);
-        if (more) {
+        for (int u = 0; u < DW; ++u) {
+            const int c = cb + u;
+            if (c >= c1) break;
+            const int st = u, st1 = (u + 1) % DW, slot2 = (u + 2) % DW;     // LDS stage = register slot = chunk mod 3
+            // k-step 0
+            read_b(b[1], st, 1);
 #pragma unroll
-            for (int i = 0; i < CHUNK_U4 / 256; ++i) lds[0][i * 256 + threadIdx.x] = a[i];
+            for (int i = 0; i < A_PER_THREAD; ++i) lds[st1][i * 256 + threadIdx.x] = a[i];
+            mfmas(w[u][0], b[0]);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, NT, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_DSW, 1, 0);
+            }
+            // k-step 1
+            read_b(b[0], st, 2);
+            load_a(a, c + 2);
+            mfmas(w[u][1], b[1]);
+#pragma unroll
+            for (int g = 0; g < 8; ++g) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, NT, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
+            }
+            __syncthreads();                    // chunk c+1 is staged; stage (c+2) mod 3 is free again
+            // k-step 2
+            read_b(b[1], st, 3);
+            load_w(w[slot2], c + 2, 0, KC / 2);
+            mfmas(w[u][2], b[0]);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2 * NT, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_VMEM, NT == 2 ? 1 : 1, 0);
+            }
+            // k-step 3 (reads the first fragments of the next chunk)
+            read_b(b[0], st1, 0);
+            load_w(w[slot2], c + 2, KC / 2, KC);
+            mfmas(w[u][3], b[1]);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2 * NT, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
+            }
         }
-        __syncthreads();
     }
     // C^T accumulator layout of the 32x32 MFMA: register r of lane l holds
     //   weight row n = 8*(r/4) + 4*(l/32) + r%4 of the tile, activation row m = l%32.
@@ -155,14 +194,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const u32x4* __restrict__ Wt,
 
 // nt: weight tiles of 32 rows per wave (workgroup tile = 128 * nt columns); forced values <= 0 = choose.
 GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
-    const int n_tiles = N / 32, mt_total = (m_rows + 31) / 32, ksteps = K / 16;
-    const int m_groups = (mt_total + MT - 1) / MT, total_chunks = (ksteps + KC - 1) / KC;
+    const int n_tiles = N / 32, mt_total = (m_rows + 31) / 32, ksteps = (K + 63) / 64 * 4;
+    const int m_groups = (mt_total + MT - 1) / MT, total_chunks = ksteps / KC;
     GemmPlan p;
     p.nt = forced_nt > 0 ? forced_nt : (n_tiles >= 8 ? 2 : 1);
     if (forced_nt <= 0 && m_groups == 1 && N <= 8192) p.nt = 1;     // few columns: narrower tiles, fewer splits
     if (p.nt == 2 && n_tiles < 8) p.nt = 1;
     const int n_groups = (n_tiles + 4 * p.nt - 1) / (4 * p.nt), base = n_groups * m_groups;
-    int split = forced_split > 0 ? forced_split : (base >= 192 ? 1 : (256 + base - 1) / base);
+    // one workgroup per CU (256 CUs): split k so that the grid stays within one round of workgroups
+    int split = forced_split > 0 ? forced_split : (base >= 256 ? 1 : 256 / base);
     if (split > BB_MAX_SPLITK) split = BB_MAX_SPLITK;
     if (split > total_chunks / 4) split = total_chunks / 4;
     if (split < 1) split = 1;
@@ -172,7 +212,7 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
 }
 
 void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s) {
-    const int n_tiles = N / 32, ksteps = K / 16, m_groups = (mt_total + MT - 1) / MT;
+    const int n_tiles = N / 32, ksteps = (K + 63) / 64 * 4, m_groups = (mt_total + MT - 1) / MT;     // K padded to whole chunks
     const size_t split_stride = (size_t)mt_total * 32 * N;
     if (plan.nt == 2) {
         dim3 grid((n_tiles + 7) / 8, m_groups, plan.split_k);
@@ -186,30 +226,32 @@ void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int 
 // ---- weight re-tiling (load time) and activation packing ------------------------------------------
 // interleave != 0: source row r goes to fused row (r / 64) * 128 + r % 64 + row0 (gate rows with
 // row0 = 0, up rows with row0 = 64), so a GEMM tile of 128 or 256 columns holds both halves of its features.
+// The destination is laid out for K padded to a multiple of 64 (whole chunks); the padding must be zero.
 __global__ void tile_weights_kernel(const u32x4* __restrict__ src, int rows, int k8s, u32x4* __restrict__ dst, int row0,
-                                    int interleave) {
+                                    int interleave, int ksteps_pad) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)rows * k8s) return;
     int r = (int)(i / k8s), k8 = (int)(i % k8s);
     int n = interleave ? (r / 64) * 128 + r % 64 + row0 : row0 + r;
-    dst[tileW_u4(n, k8, k8s / 2)] = src[i];
+    dst[tileW_u4(n, k8, ksteps_pad)] = src[i];
 }
 
 void launch_tile_weights(const uint16_t* src, int rows, int K, u32x4* dst, int dst_row0, int interleave, hipStream_t s) {
     size_t n = (size_t)rows * (K / 8);
-    tile_weights_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(reinterpret_cast<const u32x4*>(src), rows, K / 8, dst, dst_row0, interleave);
+    tile_weights_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(reinterpret_cast<const u32x4*>(src), rows, K / 8, dst, dst_row0,
+                                                                    interleave, (K + 63) / 64 * 4);
 }
 
-// fp32 row-major [M][K] -> packed hi/lo fragments; rows >= M inside the last tile are zero.
+// fp32 row-major [M][K] -> packed hi/lo fragments; rows >= M and columns >= K (padding to whole chunks) are zero.
 __global__ void pack_rows_kernel(const float* __restrict__ A, int M, int K, u32x4* __restrict__ Apk, int mt_total) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int k8s = K / 8;
+    int k8s = (K + 63) / 64 * 8;
     if (i >= (size_t)mt_total * 32 * k8s) return;
     int m = (int)(i / k8s), k8 = (int)(i % k8s);
     uint16_t hi[8], lo[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        float x = m < M ? A[(size_t)m * K + k8 * 8 + j] : 0.f;
+        float x = m < M && k8 * 8 < K ? A[(size_t)m * K + k8 * 8 + j] : 0.f;
         hi[j] = f32_to_bf16_rne(x);
         lo[j] = f32_to_bf16_rne(x - bf16_to_f32(hi[j]));
     }
@@ -218,6 +260,6 @@ __global__ void pack_rows_kernel(const float* __restrict__ A, int M, int K, u32x
 }
 
 void launch_pack_rows(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s) {
-    size_t n = (size_t)mt_total * 32 * (K / 8);
+    size_t n = (size_t)mt_total * 32 * ((K + 63) / 64 * 8);
     pack_rows_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(A, M, K, Apk, mt_total);
 }
