@@ -214,9 +214,11 @@ extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decod
     size_t zero_bytes = (char*)c->emb - c->ws;
     hipError_t e = hipMemsetAsync(c->ws, 0, zero_bytes, c->stream);
     if (e != hipSuccess) { delete c; return BB_EHIP; }
-    if (model->d_ffn % 64)                              // padded gate/up rows must be finite
-        for (auto& L : c->layers)
+    if (model->d_ffn % 64)            // padded gate/up rows and the down projection's padded k columns must be zero
+        for (auto& L : c->layers) {
             if (e == hipSuccess) e = hipMemsetAsync(L.wgu, 0, (size_t)c->ngu * model->d_model * 2, c->stream);
+            if (e == hipSuccess) e = hipMemsetAsync(L.wdown, 0, (size_t)model->d_model * ((model->d_ffn + 63) / 64 * 64) * 2, c->stream);
+        }
     if (e != hipSuccess) { delete c; return BB_EHIP; }
     // rotary table in double precision on the host
     const int half = model->head_dim / 2, lpad = c->D.lpad;

@@ -10,6 +10,7 @@
 // is split over several workgroups to occupy every CU; each writes its partial tile and the
 // consumer kernel (residual + norm, SwiGLU, bias + RoPE + cache write) sums them in split order.
 #include "bb_internal.h"
+#include <type_traits>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -121,56 +122,62 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     __syncthreads();
     read_b(b[0], 0, 0);
 
-    for (int cb = c0; cb < c1; cb += DW) {
+    // One chunk of the pipeline; U = (c - c0) mod 3 selects LDS stage and register slot statically.
+    auto chunk = [&](auto U, int c) {
+        constexpr int u = decltype(U)::value, st = u, st1 = (u + 1) % DW, slot2 = (u + 2) % DW;
+        // k-step 0
+        read_b(b[1], st, 1);
 #pragma unroll
-        for (int u = 0; u < DW; ++u) {
-            const int c = cb + u;
-            if (c >= c1) break;
-            const int st = u, st1 = (u + 1) % DW, slot2 = (u + 2) % DW;     // LDS stage = register slot = chunk mod 3
-            // k-step 0
-            read_b(b[1], st, 1);
+        for (int i = 0; i < A_PER_THREAD; ++i) lds[st1][i * 256 + threadIdx.x] = a[i];
+        mfmas(w[u][0], b[0]);
 #pragma unroll
-            for (int i = 0; i < A_PER_THREAD; ++i) lds[st1][i * 256 + threadIdx.x] = a[i];
-            mfmas(w[u][0], b[0]);
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, NT, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_DSW, 1, 0);
-            }
-            // k-step 1
-            read_b(b[0], st, 2);
-            load_a(a, c + 2);
-            mfmas(w[u][1], b[1]);
-#pragma unroll
-            for (int g = 0; g < 8; ++g) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, NT, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
-            }
-            __syncthreads();                    // chunk c+1 is staged; stage (c+2) mod 3 is free again
-            // k-step 2
-            read_b(b[1], st, 3);
-            load_w(w[slot2], c + 2, 0, KC / 2);
-            mfmas(w[u][2], b[0]);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2 * NT, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_VMEM, NT == 2 ? 1 : 1, 0);
-            }
-            // k-step 3 (reads the first fragments of the next chunk)
-            read_b(b[0], st1, 0);
-            load_w(w[slot2], c + 2, KC / 2, KC);
-            mfmas(w[u][3], b[1]);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2 * NT, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
-            }
+        for (int g = 0; g < 8; ++g) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, NT, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DSW, 1, 0);
         }
+        // k-step 1
+        read_b(b[0], st, 2);
+        load_a(a, c + 2);
+        mfmas(w[u][1], b[1]);
+#pragma unroll
+        for (int g = 0; g < 8; ++g) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, NT, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DSR, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
+        }
+        __syncthreads();                    // chunk c+1 is staged; stage (c+2) mod 3 is free again
+        // k-step 2
+        read_b(b[1], st, 3);
+        load_w(w[slot2], c + 2, 0, KC / 2);
+        mfmas(w[u][2], b[0]);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2 * NT, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
+        }
+        // k-step 3 (reads the first fragments of the next chunk)
+        read_b(b[0], st1, 0);
+        load_w(w[slot2], c + 2, KC / 2, KC);
+        mfmas(w[u][3], b[1]);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            __builtin_amdgcn_sched_group_barrier(SG_MFMA, 2 * NT, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_DSR, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(SG_VMEM, 1, 0);
+        }
+    };
+    // The steady-state loop has no branch inside a triple of chunks: with one the compiler sinks the
+    // weight loads next to their uses in the later block and the prefetch distance is lost.
+    int c = c0;
+    for (; c + DW <= c1; c += DW) {
+        chunk(std::integral_constant<int, 0>{}, c);
+        chunk(std::integral_constant<int, 1>{}, c + 1);
+        chunk(std::integral_constant<int, 2>{}, c + 2);
     }
+    if (c < c1) chunk(std::integral_constant<int, 0>{}, c);
+    if (c + 1 < c1) chunk(std::integral_constant<int, 1>{}, c + 1);
     // C^T accumulator layout of the 32x32 MFMA: register r of lane l holds
     //   weight row n = 8*(r/4) + 4*(l/32) + r%4 of the tile, activation row m = l%32.
     float* Ps = P + (size_t)blockIdx.z * split_stride;
