@@ -31,10 +31,11 @@ static __device__ __forceinline__ f16x8 as_f16x8(const u32x4& v) { return *reint
 
 template <int HD, bool SPLITQ>
 __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __restrict__ Q, u32x4* __restrict__ Apk,
-                                                        int layer, int mt_total, int seg_base) {
+                                                        int layer, int mt_total, int seg_base, int n_splits,
+                                                        float* __restrict__ part) {
     constexpr int KS = HD / 16;         // k-steps of the score contraction
     constexpr int DT = HD / 32;         // 32-wide tiles of the output's head dimension
-    __shared__ float sO[4][32][HD + 4];
+    __shared__ float sO[4][32][HD + 1];
     __shared__ float sM[4][32], sL[4][32];
 
     const int gbr = seg_base + blockIdx.z;
@@ -42,7 +43,9 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     if (seg_rows == 0) return;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
     const int group = D.hq / D.hkv, nflat = seg_rows * group;
-    const int wg_base = blockIdx.x * (SPLITQ ? 128 : 32);
+    // block steps may also split a row's pages over n_splits workgroups (blockIdx.x = tile * n_splits + split)
+    const int split = SPLITQ ? 0 : blockIdx.x % n_splits, qtile = SPLITQ ? blockIdx.x : blockIdx.x / n_splits;
+    const int wg_base = qtile * (SPLITQ ? 128 : 32);
     if (wg_base >= nflat) return;
     const int tile_base = SPLITQ ? wg_base + 32 * wave : wg_base;     // this wave's 32 query rows
     const int kvh = blockIdx.y, seg_off = D.seg_off[gbr];
@@ -50,18 +53,20 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
     const float scale = 1.0f / sqrtf((float)HD);
 
-    // Q fragments (B operand): lane (query c, k group g) holds 8 consecutive head dims per k-step.
+    // Q fragments (B operand).  The contraction index may be enumerated in any order as long as K uses the
+    // same one: k-step ks, lane group g, slot j  <->  head dim (HD/2) g + 8 ks + j, so a lane's KS fragments
+    // of a row are one contiguous run of HD/2 values (whole cache lines instead of 16-byte pieces).
     u32x4 qf[2][KS];                    // [term][k-step]
     {
         const int f = tile_base + c;
         const bool ok = f < nflat;
         const int hig = ok ? f / seg_rows : 0, r = ok ? f % seg_rows : 0;
-        const half_t* qp = Q + ((size_t)(seg_off + r) * D.hq + kvh * group + hig) * 2 * HD + 8 * g;
+        const half_t* qp = Q + ((size_t)(seg_off + r) * D.hq + kvh * group + hig) * 2 * HD + (HD / 2) * g;
 #pragma unroll
         for (int term = 0; term < 2; ++term)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                qf[term][ks] = ok ? *reinterpret_cast<const u32x4*>(qp + term * HD + 16 * ks) : u32x4{0u, 0u, 0u, 0u};
+                qf[term][ks] = ok ? *reinterpret_cast<const u32x4*>(qp + term * HD + 8 * ks) : u32x4{0u, 0u, 0u, 0u};
     }
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 o[DT];
@@ -70,24 +75,29 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
 
-    const int p0 = SPLITQ ? 0 : wave, pstep = SPLITQ ? 1 : 4;
+    const int pps = (n_pages + n_splits - 1) / n_splits;           // pages per split
+    const int p0 = SPLITQ ? 0 : split * pps + wave, pstep = SPLITQ ? 1 : 4;
+    const int p1 = SPLITQ ? n_pages : min(n_pages, (split + 1) * pps);
     const bool active = tile_base < nflat;          // SPLITQ: trailing waves may have no rows
-    for (int page = p0; page < n_pages && active; page += pstep) {
+    for (int page = p0; page < p1 && active; page += pstep) {
         const int phys = D.table[(size_t)gbr * D.n_pages + page];
         const int t0 = page * BB_PAGE;
         const half_t* Kb = D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + t0) * D.hkv + kvh) * 2 * HD;
         const half_t* Vb = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + kvh) * 2 * HD * (size_t)D.lpad + t0;
-        // scores: two tiles of 32 keys.  Register r of s[kt]: key t0 + 32 kt + 8 (r/4) + 4 g + r%4, query c.
+        // scores: two tiles of 32 keys.  MFMA row i of a tile is given key pi(i) = i%4 + 4 (i/8) + 16 ((i/4)%2),
+        // which makes the 16 accumulator registers of a lane the 16 consecutive keys t0 + 32 kt + 16 g + r
+        // (query c), so the matching V^T fragments are contiguous 16-byte loads.
         f32x16 s[2];
+        const int krow = (c & 3) + 4 * (c >> 3) + 16 * ((c >> 2) & 1);
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-            const half_t* kp = Kb + (size_t)(32 * kt + c) * D.hkv * 2 * HD + 8 * g;
+            const half_t* kp = Kb + (size_t)(32 * kt + krow) * D.hkv * 2 * HD + (HD / 2) * g;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const f16x8 kh = as_f16x8(*reinterpret_cast<const u32x4*>(kp + 16 * ks));
-                const f16x8 kl = as_f16x8(*reinterpret_cast<const u32x4*>(kp + HD + 16 * ks));
+                const f16x8 kh = as_f16x8(*reinterpret_cast<const u32x4*>(kp + 8 * ks));
+                const f16x8 kl = as_f16x8(*reinterpret_cast<const u32x4*>(kp + HD + 8 * ks));
                 s[kt] = MFMA16(kl, as_f16x8(qf[0][ks]), s[kt]);
                 s[kt] = MFMA16(kh, as_f16x8(qf[1][ks]), s[kt]);
                 s[kt] = MFMA16(kh, as_f16x8(qf[0][ks]), s[kt]);
@@ -98,7 +108,7 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int key = t0 + 32 * kt + 8 * (r >> 2) + 4 * g + (r & 3);
+                const int key = t0 + 32 * kt + 16 * g + r;
                 const float v = key < L ? s[kt][r] * scale : -INFINITY;
                 s[kt][r] = v;
                 mx = fmaxf(mx, v);
@@ -107,7 +117,7 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
         const float m_new = fmaxf(m_run, mx);               // finite: every page holds a valid key
         const float alpha = expf(m_run - m_new);            // exp(-inf) = 0 on the first page
         float sum = 0.f;
-        // P fragment kk (16 keys): slot j holds key 32 (kk/2) + 16 (kk%2) + 4 g + j (j < 4) or + 8 + 4 g + (j - 4)
+        // P fragment kk = 2 kt + h (16 keys of the contraction): slot j of lane group g holds key 32 kt + 16 g + 8 h + j
         f16x8 ph[4], pl[4];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
@@ -125,17 +135,12 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
         for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            const half_t* vp = Vb + (size_t)(32 * dt + c) * D.lpad + 4 * g;
+            const half_t* vp = Vb + (size_t)(32 * dt + c) * D.lpad + 16 * g;
             const half_t* vq = vp + (size_t)HD * D.lpad;        // lo term
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                f16x8 vh, vl;
-                const f16x4 h0 = *reinterpret_cast<const f16x4*>(vp + 16 * kk);
-                const f16x4 h1 = *reinterpret_cast<const f16x4*>(vp + 16 * kk + 8);
-                const f16x4 l0 = *reinterpret_cast<const f16x4*>(vq + 16 * kk);
-                const f16x4 l1 = *reinterpret_cast<const f16x4*>(vq + 16 * kk + 8);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) { vh[j] = h0[j]; vh[4 + j] = h1[j]; vl[j] = l0[j]; vl[4 + j] = l1[j]; }
+                const f16x8 vh = as_f16x8(*reinterpret_cast<const u32x4*>(vp + 32 * (kk >> 1) + 8 * (kk & 1)));
+                const f16x8 vl = as_f16x8(*reinterpret_cast<const u32x4*>(vq + 32 * (kk >> 1) + 8 * (kk & 1)));
                 o[dt] = MFMA16(vl, ph[kk], o[dt]);
                 o[dt] = MFMA16(vh, pl[kk], o[dt]);
                 o[dt] = MFMA16(vh, ph[kk], o[dt]);
@@ -156,6 +161,28 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     // bf16 hi/lo and store as the O-projection's packed activation panel (row = packed query row,
     // k = head * HD + d).
     constexpr int ROWS = SPLITQ ? 128 : 32;
+    if (!SPLITQ && n_splits > 1) {
+        // unnormalised partial result of this split: max[32], sum[32], O[32][HD]; attention_combine_kernel finishes
+        float* dst = part + ((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * (gridDim.x / n_splits) + qtile) * n_splits + split) * (64 + 32 * HD);
+        for (int item = threadIdx.x; item < 32 * (HD / 4); item += 256) {
+            const int q = item / (HD / 4), d4 = item % (HD / 4);
+            float M = sM[0][q];
+            for (int w = 1; w < 4; ++w) M = fmaxf(M, sM[w][q]);
+            float wgt[4], lsum = 0.f;
+            for (int w = 0; w < 4; ++w) {
+                wgt[w] = sM[w][q] == -INFINITY ? 0.f : expf(sM[w][q] - M);
+                lsum += wgt[w] * sL[w][q];
+            }
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int w = 0; w < 4; ++w) {
+                acc.x += wgt[w] * sO[w][q][d4 * 4 + 0]; acc.y += wgt[w] * sO[w][q][d4 * 4 + 1];
+                acc.z += wgt[w] * sO[w][q][d4 * 4 + 2]; acc.w += wgt[w] * sO[w][q][d4 * 4 + 3];
+            }
+            *reinterpret_cast<float4*>(dst + 64 + q * HD + d4 * 4) = acc;
+            if (d4 == 0) { dst[q] = M; dst[32 + q] = lsum; }
+        }
+        return;
+    }
     for (int item = threadIdx.x; item < ROWS * (HD / 8); item += 256) {
         const int q = item / (HD / 8), d8 = item % (HD / 8);
         const int f = wg_base + q;
@@ -195,16 +222,70 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     }
 }
 
+// Merge the splits of one tile in split order, normalise, and store the packed hi/lo panel.
+template <int HD>
+__global__ __launch_bounds__(256) void attention_combine_kernel(Dev D, const float* __restrict__ part, u32x4* __restrict__ Apk,
+                                                                int mt_total, int seg_base, int n_splits) {
+    const int gbr = seg_base + blockIdx.z;
+    const int seg_rows = D.seg_rows[gbr];
+    if (seg_rows == 0) return;
+    const int group = D.hq / D.hkv, nflat = seg_rows * group, wg_base = blockIdx.x * 32;
+    if (wg_base >= nflat) return;
+    const int kvh = blockIdx.y, seg_off = D.seg_off[gbr];
+    const float* src = part + (((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * n_splits * (64 + 32 * HD);
+    for (int item = threadIdx.x; item < 32 * (HD / 8); item += 256) {
+        const int q = item / (HD / 8), d8 = item % (HD / 8);
+        const int f = wg_base + q;
+        if (f >= nflat) continue;
+        float M = -INFINITY;
+        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, src[s * (64 + 32 * HD) + q]);
+        float lsum = 0.f, y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < n_splits; ++s) {
+            const float* ps = src + s * (64 + 32 * HD);
+            const float ms = ps[q], wgt = ms == -INFINITY ? 0.f : expf(ms - M);
+            lsum += wgt * ps[32 + q];
+            const float4 a = *reinterpret_cast<const float4*>(ps + 64 + q * HD + d8 * 8);
+            const float4 b = *reinterpret_cast<const float4*>(ps + 64 + q * HD + d8 * 8 + 4);
+            y[0] += wgt * a.x; y[1] += wgt * a.y; y[2] += wgt * a.z; y[3] += wgt * a.w;
+            y[4] += wgt * b.x; y[5] += wgt * b.y; y[6] += wgt * b.z; y[7] += wgt * b.w;
+        }
+        const float inv = 1.0f / lsum;
+        const int hig = f / seg_rows, r = f % seg_rows;
+        const int m = seg_off + r, k8 = ((kvh * group + hig) * HD) / 8 + d8;
+        uint16_t hi[8], lo[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float v = y[e] * inv;
+            hi[e] = f32_to_bf16_rne(v);
+            lo[e] = f32_to_bf16_rne(v - bf16_to_f32(hi[e]));
+        }
+        Apk[packA_u4(m, k8, mt_total, 0)] = *reinterpret_cast<u32x4*>(hi);
+        Apk[packA_u4(m, k8, mt_total, 1)] = *reinterpret_cast<u32x4*>(lo);
+    }
+}
+
+// max_pages: pages of the longest row among the segments; part / part_elems: scratch for split partial results.
 void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int mt_total, int max_seg_rows,
-                      int seg_base, int n_segs, hipStream_t s) {
+                      int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, hipStream_t s) {
     const int group = D.hq / D.hkv, nflat = max_seg_rows * group;
     if (nflat >= 512) {     // many query rows per segment: waves take different query tiles
         dim3 grid((nflat + 127) / 128, D.hkv, n_segs);
-        if (D.hd == 128) attention_kernel<128, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base);
-        else attention_kernel<64, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base);
+        if (D.hd == 128) attention_kernel<128, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr);
+        else attention_kernel<64, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr);
+        return;
+    }
+    // few query rows: one page per wave where the scratch allows, so the latency chain of a workgroup is short
+    const int qtiles = (nflat + 31) / 32;
+    int n_splits = (max_pages + 3) / 4;
+    if (n_splits > 16) n_splits = 16;
+    while (n_splits > 1 && (size_t)qtiles * D.hkv * n_segs * n_splits * (64 + 32 * D.hd) > part_elems) --n_splits;
+    if (n_splits < 1) n_splits = 1;
+    dim3 grid(qtiles * n_splits, D.hkv, n_segs), cgrid(qtiles, D.hkv, n_segs);
+    if (D.hd == 128) {
+        attention_kernel<128, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, n_splits, part);
+        if (n_splits > 1) attention_combine_kernel<128><<<cgrid, 256, 0, s>>>(D, part, Apk, mt_total, seg_base, n_splits);
     } else {
-        dim3 grid((nflat + 31) / 32, D.hkv, n_segs);
-        if (D.hd == 128) attention_kernel<128, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base);
-        else attention_kernel<64, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base);
+        attention_kernel<64, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, n_splits, part);
+        if (n_splits > 1) attention_combine_kernel<64><<<cgrid, 256, 0, s>>>(D, part, Apk, mt_total, seg_base, n_splits);
     }
 }

@@ -25,7 +25,8 @@ struct bb_ctx {
     std::vector<char> loaded;           // per tensor slot
     int n_expected;
     // activations
-    float *h, *qkv, *part, *gu, *logits, *dbg;
+    float *h, *qkv, *part, *gu, *logits, *dbg, *attn_part;
+    size_t attn_part_elems;
     u32x4 *Apk, *Apk2; half_t* Q; char* stage;     // Apk2: SwiGLU output panel (written while Apk is still being read)
     size_t qkv_elems, part_elems, gu_elems, stage_bytes, dbg_bytes;
     int refresh_rows_cap, ngu;
@@ -159,6 +160,9 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     c->part = b.take<float>(c->part_elems);
     c->gu = b.take<float>(c->gu_elems);
     c->logits = b.take<float>((size_t)lm_pad * m.vocab);
+    // split-KV partial results of block-step attention: up to 8 splits of every 32-row tile
+    c->attn_part_elems = ((size_t)l.max_step_rows * (m.n_q_heads / m.n_kv_heads) / 32 + nbr) * m.n_kv_heads * 8 * (64 + 32 * m.head_dim);
+    c->attn_part = b.take<float>(c->attn_part_elems);
     c->dbg_bytes = 2 * (size_t)lpad * m.n_kv_heads * m.head_dim * sizeof(float);
     c->dbg = b.take<float>(c->dbg_bytes / sizeof(float));
     size_t biggest = (size_t)m.vocab * m.d_model;
@@ -386,7 +390,7 @@ static int check_reqs(bb_ctx* c, const int* ids, int n, bool need_init) {
 // ---- the forward -----------------------------------------------------------------------------------
 // mode 0: block step with LM head; 1: initial full forward with LM head over lm_cap rows
 // (results broadcast to all branches); 2: cache-only refresh (stops after the last K,V write).
-static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, int n_segs, int max_seg_rows) {
+static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, int n_segs, int max_seg_rows, int max_pages) {
     const bb_model_cfg& m = c->m; const Dev& D = c->D; hipStream_t s = c->stream;
     const int d = m.d_model, nq = m.n_q_heads * m.head_dim, f = m.d_ffn, nqkv = D.nqkv, ngu = c->ngu;
     const int mt = (rows_cap + 31) / 32, rows_pad = mt * 32;
@@ -409,7 +413,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         { PROF(BB_K_GLUE, 0, 0);
           launch_qkv_epilogue(D, c->qkv, s_qkv, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s); }
         if (mode == 2 && li == m.n_layers - 1) break;
-        { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, s); }
+        { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, max_pages, c->attn_part, c->attn_part_elems, s); }
         const int s_o = gemm(1, W.wo, c->Apk, c->part, d, nq, rows_cap, mt, gk);
         { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, s); }
         const int s_gu = gemm(2, W.wgu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk);
@@ -443,8 +447,8 @@ extern "C" int bb_refresh(bb_ctx* c, const int* ids, int n, int mode) {
         if (mode == BB_INIT && R.initialised) return fail(c, BB_ESTATE, "request already initialised");
         const int slot = ids[i];
         launch_pack_refresh(c->D, slot, mode, c->stream);
-        if (mode == BB_INIT) rc = forward(c, R.L, R.G, 1, slot * c->D.max_br, 1, R.L);
-        else rc = forward(c, R.N * R.L, 0, 2, slot * c->D.max_br, R.N, R.L);
+        if (mode == BB_INIT) rc = forward(c, R.L, R.G, 1, slot * c->D.max_br, 1, R.L, (R.L + BB_PAGE - 1) / BB_PAGE);
+        else rc = forward(c, R.N * R.L, 0, 2, slot * c->D.max_br, R.N, R.L, (R.L + BB_PAGE - 1) / BB_PAGE);
         if (rc != BB_OK) return rc;
         if (mode == BB_INIT) R.initialised = 1;
     }
@@ -461,16 +465,17 @@ static void fill_view(bb_ctx* c, bb_step_view* v) {
 extern "C" int bb_denoise_step(bb_ctx* c, const int* ids, int n, bb_step_view* view) {
     int rc = check_reqs(c, ids, n, true);
     if (rc != BB_OK) return rc;
-    int rows = 0, maxb = 0;
+    int rows = 0, maxb = 0, maxL = 0;
     for (int i = 0; i < n; ++i) {
         const HostReq& R = c->reqs[ids[i]];
+        maxL = std::max(maxL, R.L);
         for (int k = 0; k < R.N; ++k) { rows += std::min(R.blocks[k], R.G); maxb = std::max(maxb, std::min(R.blocks[k], R.G)); }
     }
     if (rows > c->lim.max_step_rows) return fail(c, BB_ENOMEM, "step rows exceed max_step_rows");
     if ((rc = upload_req_list(c, ids, n)) != BB_OK) return rc;
     { PROF(BB_K_GLUE, 0, 0); launch_pack_step(c->D, n, c->stream); }
     { PROF(BB_K_POLICY, 0, 0); launch_page_copies(c->D, c->stream); }
-    rc = forward(c, rows, rows, 0, 0, c->D.max_req * c->D.max_br, maxb);
+    rc = forward(c, rows, rows, 0, 0, c->D.max_req * c->D.max_br, maxb, (maxL + BB_PAGE - 1) / BB_PAGE);
     if (rc == BB_OK && view) fill_view(c, view);
     return rc;
 }

@@ -105,7 +105,7 @@ void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t p
 void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
                             int rows_cap, int mt_total, hipStream_t s);
 void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int mt_total, int max_seg_rows,
-                      int seg_base, int n_segs, hipStream_t s);
+                      int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, hipStream_t s);
 void launch_vocab_reduce(const Dev& D, const float* logits, int lm_cap, int bcast, hipStream_t s);
 
 void launch_pack_step(const Dev& D, int n_req, hipStream_t s);
