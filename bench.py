@@ -29,6 +29,8 @@ def main():
     ap.add_argument("--workload", default="llada")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); --gpus must be 1", file=sys.stderr)
@@ -140,6 +142,12 @@ def main():
     bb.close()
     del bb
     torch.cuda.empty_cache()
+    if args.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- 5. the CPU oracle on the host cores (reported baseline, bounded sample) ----------------------
     if not args.no_cpu_baseline:
