@@ -11,6 +11,7 @@
 // consumer kernel (residual + norm, SwiGLU, bias + RoPE + cache write) sums them in split order.
 #include "bb_internal.h"
 #include <type_traits>
+#include <algorithm>
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -48,21 +49,25 @@ static __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
 template <int NT>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ Wt, const u32x4* __restrict__ Apk,
                                                       float* __restrict__ P, size_t split_stride, int ldp, int mt_total,
-                                                      int n_tiles, int ksteps, int chunks_per_split) {
+                                                      int n_tiles, int ksteps, int chunks_per_split, int tiles_x, int tiles_y) {
     __shared__ u32x4 lds[3][CHUNK_U4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int mt0 = blockIdx.y * MT;
+    // a workgroup walks the (column group, row group) tiles with the grid's stride: at most one round of
+    // workgroups is ever launched, the rest of the tiles are taken by the same workgroups
+    for (int tile = blockIdx.x; tile < tiles_x * tiles_y; tile += gridDim.x) {
+    const int bx = tile % tiles_x, by = tile / tiles_x;
+    const int mt0 = by * MT;
     const int mt_cnt = min(MT, mt_total - mt0);
     const int total_chunks = ksteps / KC;
     const int c0 = blockIdx.z * chunks_per_split;
     const int c1 = min(c0 + chunks_per_split, total_chunks);
-    if (c0 >= c1) return;
+    if (c0 >= c1) continue;
 
     // weight stream: one pointer per tile, advanced by a chunk (KC fragments of 64 lanes) at a time
     const u32x4* wbase[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        const int x = min((int)(blockIdx.x * 4 + wave) * NT + t, n_tiles - 1);      // clamped loads; stores are guarded
+        const int x = min((bx * 4 + wave) * NT + t, n_tiles - 1);      // clamped loads; stores are guarded
         wbase[t] = Wt + (size_t)x * ksteps * 64 + lane;
     }
     // activation stream: per-thread offsets inside a chunk (missing m-tiles read a valid one)
@@ -180,22 +185,38 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     if (c + 1 < c1) chunk(std::integral_constant<int, 1>{}, c + 1);
     // C^T accumulator layout of the 32x32 MFMA: register r of lane l holds
     //   weight row n = 8*(r/4) + 4*(l/32) + r%4 of the tile, activation row m = l%32.
+    // The tile goes through LDS (each wave its own slice, two m-tiles at a time) so that the global
+    // stores are whole 128-byte lines of a row instead of 16-byte pieces of 32 different rows.
+    constexpr int COLS = 32 * NT, LDT = COLS + 4;          // row stride in floats (16-byte aligned, conflict-free)
+    __syncthreads();                                        // all waves are done with the staged activations
+    float* tl = reinterpret_cast<float*>(&lds[0][0]) + wave * (64 * LDT);
     float* Ps = P + (size_t)blockIdx.z * split_stride;
+    const int x0 = (bx * 4 + wave) * NT;                    // first weight tile of this wave
 #pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        int x = (blockIdx.x * 4 + wave) * NT + t;
-        if (x >= n_tiles) continue;
+    for (int half = 0; half < 2; ++half) {
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if (mt >= mt_cnt) continue;
-            size_t m = (size_t)(mt0 + mt) * 32 + (lane & 31);
+        for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                int n = x * 32 + 8 * q + 4 * (lane >> 5);
-                float4 v = make_float4(acc[t][mt][4 * q], acc[t][mt][4 * q + 1], acc[t][mt][4 * q + 2], acc[t][mt][4 * q + 3]);
-                *reinterpret_cast<float4*>(&Ps[m * ldp + n]) = v;
-            }
+            for (int mh = 0; mh < 2; ++mh)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const f32x16& a4 = acc[t][2 * half + mh];
+                    *reinterpret_cast<float4*>(&tl[(mh * 32 + (lane & 31)) * LDT + t * 32 + 8 * q + 4 * (lane >> 5)]) =
+                        make_float4(a4[4 * q], a4[4 * q + 1], a4[4 * q + 2], a4[4 * q + 3]);
+                }
+        // (same wave wrote and reads: no barrier needed, the LDS counter orders them)
+        constexpr int LPR = COLS / 4;                       // lanes per row
+        const int rows_valid = min(64, (mt_cnt - 2 * half) * 32);
+#pragma unroll
+        for (int it = 0; it < 64 * LPR / 64; ++it) {
+            const int r = it * (64 / LPR) + lane / LPR, c4 = (lane % LPR) * 4;
+            const float4 v = *reinterpret_cast<const float4*>(&tl[r * LDT + c4]);
+            const int n = x0 * 32 + c4;
+            if (r < rows_valid && n < n_tiles * 32)
+                *reinterpret_cast<float4*>(&Ps[(size_t)((mt0 + 2 * half) * 32 + r) * ldp + n]) = v;
         }
+    }
+    __syncthreads();                                        // the next tile's prologue overwrites the LDS slices
     }
 }
 
@@ -208,8 +229,21 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
     if (forced_nt <= 0 && m_groups == 1 && N <= 8192) p.nt = 1;     // few columns: narrower tiles, fewer splits
     if (p.nt == 2 && n_tiles < 8) p.nt = 1;
     const int n_groups = (n_tiles + 4 * p.nt - 1) / (4 * p.nt), base = n_groups * m_groups;
-    // one workgroup per CU (256 CUs): split k so that the grid stays within one round of workgroups
-    int split = forced_split > 0 ? forced_split : (base >= 256 ? 1 : 256 / base);
+    // One workgroup per CU (256 CUs).  Few tiles: split k so that one round of workgroups covers the chip.
+    // Many tiles: split k only if filling the last round pays for writing and re-reading the extra partial tiles.
+    int split = forced_split;
+    if (split <= 0) {
+        if (base < 256) split = 256 / base;
+        else {
+            double best = 1e30;
+            for (int sp = 1; sp <= 4; ++sp) {
+                const double units = (double)base * sp, rounds = (double)(((long)base * sp + 255) / 256);
+                const double t = 4.0 * mt_total * 32 * (double)N * K / 1.4e15 * (rounds * 256 / units)
+                               + (sp - 1) * 8.0 * mt_total * 32 * (double)N / 3e12;
+                if (t < best) { best = t; split = sp; }
+            }
+        }
+    }
     if (split > BB_MAX_SPLITK) split = BB_MAX_SPLITK;
     if (split > total_chunks / 4) split = total_chunks / 4;
     if (split < 1) split = 1;
@@ -221,18 +255,14 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
 void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s) {
     const int n_tiles = N / 32, ksteps = (K + 63) / 64 * 4, m_groups = (mt_total + MT - 1) / MT;     // K padded to whole chunks
     const size_t split_stride = (size_t)mt_total * 32 * N;
-    if (plan.nt == 2) {
-        dim3 grid((n_tiles + 7) / 8, m_groups, plan.split_k);
-        gemm_kernel<2><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split);
-    } else {
-        dim3 grid((n_tiles + 3) / 4, m_groups, plan.split_k);
-        gemm_kernel<1><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split);
-    }
+    const int tiles_x = (n_tiles + 4 * plan.nt - 1) / (4 * plan.nt);
+    dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
+    if (plan.nt == 2)
+        gemm_kernel<2><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups);
+    else
+        gemm_kernel<1><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups);
 }
 
-// ---- weight re-tiling (load time) and activation packing ------------------------------------------
-// interleave != 0: source row r goes to fused row (r / 64) * 128 + r % 64 + row0 (gate rows with
-// row0 = 0, up rows with row0 = 64), so a GEMM tile of 128 or 256 columns holds both halves of its features.
 // The destination is laid out for K padded to a multiple of 64 (whole chunks); the padding must be zero.
 __global__ void tile_weights_kernel(const u32x4* __restrict__ src, int rows, int k8s, u32x4* __restrict__ dst, int row0,
                                     int interleave, int ksteps_pad) {
