@@ -21,6 +21,7 @@
 //                                                    accumulators (same lane owns the same
 //                                                    query), keys permuted consistently.
 #include "bb_internal.h"
+#include <algorithm>
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -30,7 +31,7 @@ static __device__ __forceinline__ f16x8 as_f16x8(const u32x4& v) { return *reint
 #define MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
 
 template <int HD, bool SPLITQ>
-__global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __restrict__ Q, u32x4* __restrict__ Apk,
+__global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* __restrict__ Q, u32x4* __restrict__ Apk,
                                                         int layer, int mt_total, int seg_base, int n_splits,
                                                         float* __restrict__ part) {
     constexpr int KS = HD / 16;         // k-steps of the score contraction
@@ -41,7 +42,7 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     const int gbr = seg_base + blockIdx.z;
     const int seg_rows = D.seg_rows[gbr];
     if (seg_rows == 0) return;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
     const int group = D.hq / D.hkv, nflat = seg_rows * group;
     // block steps may also split a row's pages over n_splits workgroups (blockIdx.x = tile * n_splits + split)
     const int split = SPLITQ ? 0 : blockIdx.x % n_splits, qtile = SPLITQ ? blockIdx.x : blockIdx.x / n_splits;
@@ -50,23 +51,20 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
     const int tile_base = SPLITQ ? wg_base + 32 * wave : wg_base;     // this wave's 32 query rows
     const int kvh = blockIdx.y, seg_off = D.seg_off[gbr];
     const int L = D.hdr[gbr / D.max_br].L, n_pages = (L + BB_PAGE - 1) / BB_PAGE;
-    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
     const float scale = 1.0f / sqrtf((float)HD);
 
     // Q fragments (B operand).  The contraction index may be enumerated in any order as long as K uses the
     // same one: k-step ks, lane group g, slot j  <->  head dim (HD/2) g + 8 ks + j, so a lane's KS fragments
-    // of a row are one contiguous run of HD/2 values (whole cache lines instead of 16-byte pieces).
+    // of a row are one contiguous run of HD/2 values.  Rows past the end repeat the last row (never stored).
     u32x4 qf[2][KS];                    // [term][k-step]
     {
-        const int f = tile_base + c;
-        const bool ok = f < nflat;
-        const int hig = ok ? f / seg_rows : 0, r = ok ? f % seg_rows : 0;
+        const int f = min(tile_base + c, nflat - 1);
+        const int hig = f / seg_rows, r = f % seg_rows;
         const half_t* qp = Q + ((size_t)(seg_off + r) * D.hq + kvh * group + hig) * 2 * HD + (HD / 2) * g;
 #pragma unroll
         for (int term = 0; term < 2; ++term)
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks)
-                qf[term][ks] = ok ? *reinterpret_cast<const u32x4*>(qp + term * HD + 8 * ks) : u32x4{0u, 0u, 0u, 0u};
+            for (int ks = 0; ks < KS; ++ks) qf[term][ks] = *reinterpret_cast<const u32x4*>(qp + term * HD + 8 * ks);
     }
     float m_run = -INFINITY, l_run = 0.f;
     f32x16 o[DT];
@@ -77,31 +75,45 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
 
     const int pps = (n_pages + n_splits - 1) / n_splits;           // pages per split
     const int p0 = SPLITQ ? 0 : split * pps + wave, pstep = SPLITQ ? 1 : 4;
-    const int p1 = SPLITQ ? n_pages : min(n_pages, (split + 1) * pps);
-    const bool active = tile_base < nflat;          // SPLITQ: trailing waves may have no rows
-    for (int page = p0; page < p1 && active; page += pstep) {
+    const int p1 = (SPLITQ ? tile_base < nflat : true) ? (SPLITQ ? n_pages : min(n_pages, (split + 1) * pps)) : 0;
+    // A page's K and V fragments (NF x 1 KiB each way) pass through one ring of NF registers-fragments in halves:
+    // K tile 0 | K tile 1 -> V dims low | V dims high -> next page's K tile 0 | ...  Each half is requested as
+    // soon as the MFMAs that read the half before it have been issued, so a wave always has 16-32 KiB in
+    // flight and pays the memory latency per half page, not per fragment.
+    constexpr int NF = 2 * KS * 2, H = NF / 2;      // NF = DT * 4 * 2 as well
+    u32x4 kv[NF];
+    auto block = [&](const half_t* cache, int page) {
         const int phys = D.table[(size_t)gbr * D.n_pages + page];
-        const int t0 = page * BB_PAGE;
-        const half_t* Kb = D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + t0) * D.hkv + kvh) * 2 * HD;
-        const half_t* Vb = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + kvh) * 2 * HD * (size_t)D.lpad + t0;
-        // scores: two tiles of 32 keys.  MFMA row i of a tile is given key pi(i) = i%4 + 4 (i/8) + 16 ((i/4)%2),
+        return reinterpret_cast<const u32x4*>(cache + kv_block_off(D, layer, phys, page, kvh)) + lane;
+    };
+    auto fetch_half = [&](int h, const u32x4* src) {
+#pragma unroll
+        for (int i = 0; i < H; ++i) kv[h * H + i] = src[(h * H + i) * 64];
+    };
+    if (p0 < p1) { const u32x4* Kp = block(D.Kc, p0); fetch_half(0, Kp); fetch_half(1, Kp); }
+    for (int page = p0; page < p1; page += pstep) {
+        const int t0 = page * BB_PAGE, nxt = page + pstep;
+        const u32x4* Vp = block(D.Vt, page);
+        const u32x4* Kn = block(D.Kc, min(nxt, D.n_pages - 1));
+        // scores: two tiles of 32 keys.  The cache stores MFMA row i of a tile as key pi(i) = i%4 + 4 (i/8) + 16 ((i/4)%2),
         // which makes the 16 accumulator registers of a lane the 16 consecutive keys t0 + 32 kt + 16 g + r
-        // (query c), so the matching V^T fragments are contiguous 16-byte loads.
+        // (query c): the order of the V^T fragments' contraction index.  Fragment (kt, ks, term) = kv[(kt KS + ks) 2 + term].
         f32x16 s[2];
-        const int krow = (c & 3) + 4 * (c >> 3) + 16 * ((c >> 2) & 1);
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
-            const half_t* kp = Kb + (size_t)(32 * kt + krow) * D.hkv * 2 * HD + (HD / 2) * g;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const f16x8 kh = as_f16x8(*reinterpret_cast<const u32x4*>(kp + 8 * ks));
-                const f16x8 kl = as_f16x8(*reinterpret_cast<const u32x4*>(kp + HD + 8 * ks));
+                const f16x8 kh = as_f16x8(kv[(kt * KS + ks) * 2 + 0]);
+                const f16x8 kl = as_f16x8(kv[(kt * KS + ks) * 2 + 1]);
                 s[kt] = MFMA16(kl, as_f16x8(qf[0][ks]), s[kt]);
                 s[kt] = MFMA16(kh, as_f16x8(qf[1][ks]), s[kt]);
                 s[kt] = MFMA16(kh, as_f16x8(qf[0][ks]), s[kt]);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            fetch_half(kt, Vp);
+            __builtin_amdgcn_sched_barrier(0);
         }
         float mx = -INFINITY;
 #pragma unroll
@@ -133,17 +145,21 @@ __global__ __launch_bounds__(256) void attention_kernel(Dev D, const half_t* __r
         m_run = m_new;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+        // fragment (dt, kk, term) = kv[(dt 4 + kk) 2 + term]
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            const half_t* vp = Vb + (size_t)(32 * dt + c) * D.lpad + 16 * g;
-            const half_t* vq = vp + (size_t)HD * D.lpad;        // lo term
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                const f16x8 vh = as_f16x8(*reinterpret_cast<const u32x4*>(vp + 32 * (kk >> 1) + 8 * (kk & 1)));
-                const f16x8 vl = as_f16x8(*reinterpret_cast<const u32x4*>(vq + 32 * (kk >> 1) + 8 * (kk & 1)));
+                const f16x8 vh = as_f16x8(kv[(dt * 4 + kk) * 2 + 0]);
+                const f16x8 vl = as_f16x8(kv[(dt * 4 + kk) * 2 + 1]);
                 o[dt] = MFMA16(vl, ph[kk], o[dt]);
                 o[dt] = MFMA16(vh, pl[kk], o[dt]);
                 o[dt] = MFMA16(vh, ph[kk], o[dt]);
+            }
+            if (dt % (DT / 2) == DT / 2 - 1) {
+                __builtin_amdgcn_sched_barrier(0);
+                if (nxt < p1) fetch_half(dt / (DT / 2), Kn);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     }
@@ -274,11 +290,11 @@ void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int 
         else attention_kernel<64, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr);
         return;
     }
-    // few query rows: one page per wave where the scratch allows, so the latency chain of a workgroup is short
-    const int qtiles = (nflat + 31) / 32;
-    int n_splits = (max_pages + 3) / 4;
-    if (n_splits > 16) n_splits = 16;
-    while (n_splits > 1 && (size_t)qtiles * D.hkv * n_segs * n_splits * (64 + 32 * D.hd) > part_elems) --n_splits;
+    // few query rows: one workgroup per tile unless that leaves most of the 256 CUs idle; then the pages of a
+    // row are split over several workgroups (each wave keeps at least one page) and a second kernel merges them
+    const int qtiles = (nflat + 31) / 32, tiles = qtiles * D.hkv * n_segs;
+    int n_splits = std::min(std::min(256 / tiles, (max_pages + 3) / 4), 16);
+    while (n_splits > 1 && (size_t)tiles * n_splits * (64 + 32 * D.hd) > part_elems) --n_splits;
     if (n_splits < 1) n_splits = 1;
     dim3 grid(qtiles * n_splits, D.hkv, n_segs), cgrid(qtiles, D.hkv, n_segs);
     if (D.hd == 128) {

@@ -42,8 +42,8 @@ struct Dev {
     int* table;                 // [max_req][max_br][n_pages] -> physical cache row
     // K,V are cached as two fp16 terms (hi + lo, ~22 significant bits): one fp16 term alone
     // moves the logits of a 32-layer model by more than the parity tolerance.
-    half_t* Kc;                 // [n_layers][phys_rows][lpad][hkv][term][hd]
-    half_t* Vt;                 // [n_layers][phys_rows][hkv][term][hd][lpad]   (transposed)
+    half_t* Kc;                 // [n_layers][phys_rows][n_pages][hkv] blocks of MFMA fragments, see kv_block_off
+    half_t* Vt;                 // same, fragments of V^T
     float* map_hf;              // [max_req][max_br][gmax][d]  final-norm hidden of the latest forward
     float* map_lse;             // [max_req][max_br][gmax]
     float* map_conf;            // [max_req][max_br][gmax]
@@ -75,6 +75,29 @@ static inline __host__ __device__ size_t packA_u4(int m, int k8, int mt_total, i
 static inline __host__ __device__ size_t tileW_u4(int n, int k8, int ksteps) {
     int kstep = k8 >> 1, nt = n >> 5, lane = (n & 31) + ((k8 & 1) << 5);
     return ((size_t)nt * ksteps + kstep) * 64 + lane;
+}
+
+// ---- KV cache layout ------------------------------------------------------------------------------
+// One block = (layer, physical row, page, kv head): the page's 64 tokens stored as the MFMA A-fragments
+// (32 rows x 16 k, 64 lanes x 8 fp16 = 1 KiB each) that attention consumes, so that a wave fetches a
+// fragment with one contiguous 16-byte load per lane.
+//   K block [kt = token / 32][ks][term][lane = c + 32 g][j]: token % 32 = (c&3) + 4 (c>>3) + 16 ((c>>2)&1),
+//            head dim = (hd/2) g + 8 ks + j   (ks < hd/16);
+//   V block [dt = dim / 32][kk][term][lane = dim % 32 + 32 g][j]: token = 32 (kk/2) + 16 g + 8 (kk%2) + j.
+// The token permutation of K makes the 16 score accumulators of a lane 16 consecutive tokens, which is
+// the order the V fragments need.
+static inline __host__ __device__ size_t kv_block_off(const Dev& D, int layer, int phys, int page, int kvh) {
+    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
+    return ((((size_t)layer * phys_rows + phys) * D.n_pages + page) * D.hkv + kvh) * ((size_t)BB_PAGE * 2 * D.hd);
+}
+static inline __host__ __device__ int k_slot(int tt, int d, int term, int hd) {
+    const int kt = tt >> 5, kap = tt & 31, c = (kap & 3) | ((kap >> 4) << 2) | (((kap >> 2) & 3) << 3);
+    const int half = hd >> 1, g = d >= half, ks = (d - g * half) >> 3, j = d & 7;
+    return (((kt * (hd >> 4) + ks) * 2 + term) * 64 + c + 32 * g) * 8 + j;
+}
+static inline __host__ __device__ int v_slot(int tt, int d, int term) {
+    const int dt = d >> 5, c = d & 31, kk = 2 * (tt >> 5) + ((tt >> 3) & 1), g = (tt >> 4) & 1, j = tt & 7;
+    return (((dt * 4 + kk) * 2 + term) * 64 + c + 32 * g) * 8 + j;
 }
 
 // ---- bf16 helpers (round to nearest even, finite inputs) --------------------------------------

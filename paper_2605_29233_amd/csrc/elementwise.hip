@@ -124,11 +124,22 @@ static __device__ __forceinline__ void put2(half_t* hi_p, half_t* lo_p, float y)
     *lo_p = (half_t)(y - (float)hi);
 }
 
+// four consecutive values as hi / lo fp16 terms, 8 bytes each
+static __device__ __forceinline__ void put2x4(half_t* hi_p, half_t* lo_p, const float* y) {
+    typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+    f16x4 hi, lo;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { hi[e] = (half_t)y[e]; lo[e] = (half_t)(y[e] - (float)hi[e]); }
+    *reinterpret_cast<f16x4*>(hi_p) = hi;
+    *reinterpret_cast<f16x4*>(lo_p) = lo;
+}
+
 // QKV epilogue.  One workgroup = 16 packed rows x 128 columns (whole heads) of the fused q|k|v
 // projection: sum the split-K partials (+ bias); q and k heads are rotated by the row's
 // absolute position (pairs (j, j + hd/2), angles from a host-computed table) and stored as two
-// fp16 terms (q for the attention kernel, k into the row's cache page); v heads are transposed
-// through LDS so that the stores into the transposed cache run along the token axis.
+// fp16 terms (q for the attention kernel, k into the fragment-ordered cache page); v heads go
+// through LDS so that neighbouring lanes store neighbouring tokens of one head dim, which are adjacent
+// in the V fragments.
 __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* __restrict__ qkv, int n_partial,
                                                            size_t partial_stride, const float* __restrict__ bias,
                                                            half_t* __restrict__ Q, int layer) {
@@ -137,7 +148,6 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
     const int count = D.counts[0];
     if (m0 >= count) return;
     const int hd = D.hd, half = hd >> 1, nq = D.hq * hd, nk = D.hkv * hd;
-    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
     if (c0 < nq + nk) {
         // 16 rows x (128 / hd heads) x hd/8 groups of 4 pairs = 256 work items
         const int per_row = 16, r = t / per_row, m = m0 + r;
@@ -158,12 +168,18 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
         const float4 sn = *reinterpret_cast<const float4*>(&D.rope_sin[(size_t)pos * half + j]);
         const float a1[4] = {x1.x, x1.y, x1.z, x1.w}, a2[4] = {x2.x, x2.y, x2.z, x2.w};
         const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
-        half_t* dst = ch < nq ? Q + ((size_t)m * D.hq + ch / hd) * 2 * hd
-                              : D.Kc + ((((size_t)layer * phys_rows + D.row_phys[m]) * D.lpad + pos) * D.hkv + (ch - nq) / hd) * 2 * hd;
+        float y1[4], y2[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            put2(dst + j + e, dst + hd + j + e, a1[e] * cc[e] - a2[e] * ss[e]);
-            put2(dst + j + e + half, dst + hd + j + e + half, a2[e] * cc[e] + a1[e] * ss[e]);
+        for (int e = 0; e < 4; ++e) { y1[e] = a1[e] * cc[e] - a2[e] * ss[e]; y2[e] = a2[e] * cc[e] + a1[e] * ss[e]; }
+        if (ch < nq) {
+            half_t* dst = Q + ((size_t)m * D.hq + ch / hd) * 2 * hd;
+            put2x4(dst + j, dst + hd + j, y1);
+            put2x4(dst + j + half, dst + hd + j + half, y2);
+        } else {
+            half_t* blk = D.Kc + kv_block_off(D, layer, D.row_phys[m], pos / BB_PAGE, (ch - nq) / hd);
+            const int tt = pos % BB_PAGE;
+            put2x4(blk + k_slot(tt, j, 0, hd), blk + k_slot(tt, j, 1, hd), y1);
+            put2x4(blk + k_slot(tt, j + half, 0, hd), blk + k_slot(tt, j + half, 1, hd), y2);
         }
         return;
     }
@@ -189,9 +205,9 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
         const int c = it / 16, r = it % 16, m = m0 + r;
         if (m >= count) continue;
         const int e = c0 + c - nq - nk, head = e / hd, dd = e % hd;
-        half_t* base = D.Vt + (((size_t)layer * phys_rows + D.row_phys[m]) * D.hkv + head) * 2 * hd * (size_t)D.lpad;
-        const int pos = D.row_pos[m];
-        put2(base + (size_t)dd * D.lpad + pos, base + (size_t)(hd + dd) * D.lpad + pos, tile[c][r]);
+        const int pos = D.row_pos[m], tt = pos % BB_PAGE;
+        half_t* blk = D.Vt + kv_block_off(D, layer, D.row_phys[m], pos / BB_PAGE, head);
+        put2(blk + v_slot(tt, dd, 0), blk + v_slot(tt, dd, 1), tile[c][r]);
     }
 }
 

@@ -139,30 +139,21 @@ void launch_pack_refresh(const Dev& D, int slot, int mode, hipStream_t s) {
 }
 
 // ---- page copies (copy-on-write before a block step, row copies after a sync) ------------------
-// Work item = (list entry, layer, eighth of the page); a fixed grid strides over the items.
+// A page of one cache row is one contiguous run of hkv blocks per layer, for K and for V.
+// Work item = (list entry, layer, eighth of that run); a fixed grid strides over the items.
 __global__ __launch_bounds__(256) void page_copy_kernel(Dev D) {
     const int n = D.counts[2];
-    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
     const int items = n * D.n_layers * 8;
-    const int krow = 2 * D.hkv * D.hd;              // halfs per token in K (two terms); rows of V^T
+    const int u4s = D.hkv * BB_PAGE * 2 * D.hd / 8 / 8;      // 16-byte pieces per item
     for (int it = blockIdx.x; it < items; it += gridDim.x) {
         const int e = it / (D.n_layers * 8), layer = (it / 8) % D.n_layers, part = it % 8;
         const PageCopy pc = D.copies[e];
-        const int t0 = pc.page * BB_PAGE;
-        // K: 8 tokens of the page, contiguous
-        const size_t ks = ((((size_t)layer * phys_rows + pc.src) * D.lpad + t0 + part * 8) * krow);
-        const size_t kd = ((((size_t)layer * phys_rows + pc.dst) * D.lpad + t0 + part * 8) * krow);
-        const u32x4* s4 = reinterpret_cast<const u32x4*>(D.Kc + ks);
-        u32x4* d4 = reinterpret_cast<u32x4*>(D.Kc + kd);
-        for (int i = threadIdx.x; i < krow; i += 256) d4[i] = s4[i];          // 8 tokens * krow halfs / 8 per u32x4
-        // V^T: an eighth of the (head, dim) rows, 64 tokens (128 bytes) each
-        const int r0 = part * (krow / 8), r1 = (part + 1) * (krow / 8);
-        for (int i = threadIdx.x; i < (r1 - r0) * 8; i += 256) {
-            const int r = r0 + i / 8, q = i % 8;
-            const size_t vs = (((size_t)layer * phys_rows + pc.src) * krow + r) * D.lpad + t0 + q * 8;
-            const size_t vd = (((size_t)layer * phys_rows + pc.dst) * krow + r) * D.lpad + t0 + q * 8;
-            *reinterpret_cast<u32x4*>(D.Vt + vd) = *reinterpret_cast<const u32x4*>(D.Vt + vs);
-        }
+        const size_t so = kv_block_off(D, layer, pc.src, pc.page, 0), dof = kv_block_off(D, layer, pc.dst, pc.page, 0);
+        const u32x4* ks = reinterpret_cast<const u32x4*>(D.Kc + so) + (size_t)part * u4s;
+        const u32x4* vs = reinterpret_cast<const u32x4*>(D.Vt + so) + (size_t)part * u4s;
+        u32x4* kd = reinterpret_cast<u32x4*>(D.Kc + dof) + (size_t)part * u4s;
+        u32x4* vd = reinterpret_cast<u32x4*>(D.Vt + dof) + (size_t)part * u4s;
+        for (int i = threadIdx.x; i < u4s; i += 256) { kd[i] = ks[i]; vd[i] = vs[i]; }
     }
 }
 
@@ -405,16 +396,14 @@ void launch_commit_merge(const Dev& D, int n_req, const uint16_t* lm_head, hipSt
 
 // ---- inspection -------------------------------------------------------------------------------
 __global__ void read_kv_kernel(Dev D, int gbr, int layer, float* __restrict__ K, float* __restrict__ V, int L) {
-    const size_t phys_rows = (size_t)D.max_req * D.phys_per_req;
     const int krow = D.hkv * D.hd, hd = D.hd;
     const size_t n = (size_t)L * krow;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
         const int pos = (int)(i / krow), e = (int)(i % krow), head = e / hd, dd = e % hd;
-        const int phys = D.table[(size_t)gbr * D.n_pages + pos / BB_PAGE];
-        const half_t* kp = D.Kc + ((((size_t)layer * phys_rows + phys) * D.lpad + pos) * D.hkv + head) * 2 * hd;
-        const half_t* vp = D.Vt + (((size_t)layer * phys_rows + phys) * D.hkv + head) * 2 * hd * (size_t)D.lpad;
-        K[i] = (float)kp[dd] + (float)kp[hd + dd];
-        V[i] = (float)vp[(size_t)dd * D.lpad + pos] + (float)vp[(size_t)(hd + dd) * D.lpad + pos];
+        const int phys = D.table[(size_t)gbr * D.n_pages + pos / BB_PAGE], tt = pos % BB_PAGE;
+        const size_t blk = kv_block_off(D, layer, phys, pos / BB_PAGE, head);
+        K[i] = (float)D.Kc[blk + k_slot(tt, dd, 0, hd)] + (float)D.Kc[blk + k_slot(tt, dd, 1, hd)];
+        V[i] = (float)D.Vt[blk + v_slot(tt, dd, 0)] + (float)D.Vt[blk + v_slot(tt, dd, 1)];
     }
 }
 
