@@ -148,7 +148,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     size_t state_end = align_up(b.off, 256);
     // activations
     const int kmax = std::max(std::max(m.d_model, m.d_ffn), nq);
-    c->ngu = (m.d_ffn + 63) / 64 * 128;            // fused gate/up rows: 64 gate rows, then the 64 up rows of the same features
+    c->ngu = (m.d_ffn + 63) / 64 * 128;            // fused gate/up rows: 32 gate rows alternate with the 32 up rows of the same features; f padded to 64
     c->h = b.take<float>((size_t)rows_pad * m.d_model);
     c->Apk = b.take<u32x4>((size_t)rows_pad * kmax / 8 * BB_SPLIT);
     c->Apk2 = b.take<u32x4>((size_t)rows_pad * ((m.d_ffn + 63) / 64 * 64) / 8 * BB_SPLIT);
@@ -307,7 +307,7 @@ static int load_one(bb_ctx* c, const bb_tensor& t) {
             case 7: ok = expect(d, nq); if (ok) launch_tile_weights(src, d, nq, L.wo, 0, 0, c->stream); break;
             case 8: ok = t.rows * t.cols == d; if (ok) widen(L.g_ffn, d); break;
             case 9: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 0, 1, c->stream); break;
-            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 64, 1, c->stream); break;
+            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 32, 1, c->stream); break;
             case 11: ok = expect(d, f); if (ok) launch_tile_weights(src, d, f, L.wdown, 0, 0, c->stream); break;
         }
     } else return fail(c, BB_EINVAL, "unknown tensor " + name);
@@ -396,12 +396,16 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const int mt = (rows_cap + 31) / 32, rows_pad = mt * 32;
     const int gk = rows_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
     // kind: 0 LM head, 1 O/down, 2 gate/up, 3 QKV (index of the tuning overrides)
-    auto gemm = [&](int kind, const u32x4* W, const u32x4* A, float* P, int N, int K, int rows, int mtt, int klass) {
+    // swiglu_out: where the gate/up projection may put SiLU(gate) * up itself; it does when its k range
+    // is not split (then 0 is returned and no partial sums exist)
+    auto gemm = [&](int kind, const u32x4* W, const u32x4* A, float* P, int N, int K, int rows, int mtt, int klass,
+                    u32x4* swiglu_out = nullptr) {
         GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, c->force_nt[kind]);
         if (c->force_split[kind] > 0 && kind != 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
+        const bool fused = swiglu_out && p.split_k == 1 && p.nt == 2;
         PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-        launch_gemm(W, A, P, mtt, N, K, p, s);
-        return p.split_k;
+        launch_gemm(W, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr);
+        return fused ? 0 : p.split_k;
     };
     { PROF(BB_K_GLUE, 0, 0); launch_embed(D, c->emb, c->h, rows_cap, s); }
     int s_down = 0;
@@ -416,8 +420,8 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, max_pages, c->attn_part, c->attn_part_elems, s); }
         const int s_o = gemm(1, W.wo, c->Apk, c->part, d, nq, rows_cap, mt, gk);
         { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, s); }
-        const int s_gu = gemm(2, W.wgu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk);
-        { PROF(BB_K_GLUE, 0, 0);
+        const int s_gu = gemm(2, W.wgu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, c->Apk2);
+        if (s_gu > 0) { PROF(BB_K_GLUE, 0, 0);
           launch_swiglu_epilogue(D, c->gu, s_gu, (size_t)rows_pad * ngu, ngu, c->Apk2, rows_cap, mt, s); }
         s_down = gemm(1, W.wdown, c->Apk2, c->part, d, f, rows_cap, mt, gk);
     }

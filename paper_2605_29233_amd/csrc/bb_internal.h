@@ -113,7 +113,8 @@ static inline __host__ __device__ float bf16_to_f32(uint16_t b) {
 // ---- kernel launchers (each enqueues on `s`) -----------------------------------------------------
 struct GemmPlan { int split_k; int chunks_per_split; int nt; };
 GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt);
-void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s);
+void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s,
+                 u32x4* swiglu_out = nullptr);
 void launch_tile_weights(const uint16_t* src, int rows, int K, u32x4* dst, int dst_row0, int interleave, hipStream_t s);
 void launch_pack_rows(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);
 
@@ -124,7 +125,7 @@ void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_par
 // q,k,v = sum of partials + bias; RoPE; q -> Q, k,v -> cache rows (two fp16 terms each)
 void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t partial_stride, const float* bias,
                          half_t* Q, int layer, int rows_cap, hipStream_t s);
-// act = SiLU(gate) * up from the fused (64-row interleaved) gate/up projection -> packed panel with K = f
+// act = SiLU(gate) * up from the fused (32-row interleaved) gate/up projection -> packed panel with K = f
 void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
                             int rows_cap, int mt_total, hipStream_t s);
 void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int mt_total, int max_seg_rows,

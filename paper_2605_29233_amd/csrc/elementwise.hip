@@ -217,8 +217,8 @@ void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t p
     qkv_epilogue_kernel<<<grid, 256, 0, s>>>(D, qkv, n_partial, partial_stride, bias, Q, layer);
 }
 
-// act = SiLU(gate) * up.  The fused matrix alternates 64 gate rows with the 64 up rows of the
-// same features, so feature f has its gate in column (f / 64) * 128 + f % 64 and its up 64 further.
+// act = SiLU(gate) * up.  The fused matrix alternates 32 gate rows with the 32 up rows of the
+// same features, so feature f has its gate in column (f / 32) * 64 + f % 32 and its up 32 further.
 __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float* __restrict__ gu, int n_partial,
                                                               size_t partial_stride, int ldp, u32x4* __restrict__ Apk,
                                                               int mt_total) {
@@ -231,9 +231,9 @@ __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float
         Apk[packA_u4(m, f >> 3, mt_total, 0)] = z; Apk[packA_u4(m, f >> 3, mt_total, 1)] = z;
         return;
     }
-    const size_t off = (size_t)m * ldp + (f >> 6) * 128 + (f & 63);
+    const size_t off = (size_t)m * ldp + (f >> 5) * 64 + (f & 31);
     const float4 g0 = part_sum4(gu, n_partial, partial_stride, off), g1 = part_sum4(gu, n_partial, partial_stride, off + 4);
-    const float4 u0 = part_sum4(gu, n_partial, partial_stride, off + 64), u1 = part_sum4(gu, n_partial, partial_stride, off + 68);
+    const float4 u0 = part_sum4(gu, n_partial, partial_stride, off + 32), u1 = part_sum4(gu, n_partial, partial_stride, off + 36);
     const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
     const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
     float y[8];

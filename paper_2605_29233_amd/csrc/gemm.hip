@@ -46,10 +46,15 @@ static __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
 // Activations rotate through three LDS stages, weights through three register slots.  All loads
 // are unpredicated (indices clamped, K padded with zeros to whole chunks) so the loop body is one
 // straight block per chunk and the compiler's wait counts are exact.
-template <int NT>
+//
+// SWIGLU: the weight matrix is the fused gate/up projection (32 gate rows alternate with the 32 up rows of
+// the same features, so a wave's two tiles are gate and up of one feature group); instead of P the
+// kernel writes act = SiLU(gate) * up as the packed hi/lo panel Opk of the down projection (no k split).
+template <int NT, bool SWIGLU>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ Wt, const u32x4* __restrict__ Apk,
                                                       float* __restrict__ P, size_t split_stride, int ldp, int mt_total,
-                                                      int n_tiles, int ksteps, int chunks_per_split, int tiles_x, int tiles_y) {
+                                                      int n_tiles, int ksteps, int chunks_per_split, int tiles_x, int tiles_y,
+                                                      u32x4* __restrict__ Opk) {
     __shared__ u32x4 lds[3][CHUNK_U4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // a workgroup walks the (column group, row group) tiles with the grid's stride: at most one round of
@@ -183,6 +188,48 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     }
     if (c < c1) chunk(std::integral_constant<int, 0>{}, c);
     if (c + 1 < c1) chunk(std::integral_constant<int, 1>{}, c + 1);
+    if constexpr (SWIGLU) {
+        static_assert(!SWIGLU || NT == 2, "gate and up tiles of a feature group sit in one wave");
+        // Register r of lane (m = l%32, g = l/32) holds feature 8 (r/4) + 4 g + r%4 of the wave's 32.  The panel
+        // wants the 8 features of group q in one lane of lane-half q%2: lane halves swap the 4-feature
+        // pieces they do not own, then each lane stores the groups q = g and g + 2 (hi and lo terms).
+        const int x0 = (bx * 4 + wave) * NT, g = lane >> 5;
+        __syncthreads();                                    // the next tile's prologue overwrites the staged activations
+        if (x0 < n_tiles) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if (mt >= mt_cnt) break;
+                float act[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float gt = acc[0][mt][r], up = acc[1][mt][r];
+                    act[r] = gt / (1.0f + expf(-gt)) * up;
+                }
+#pragma unroll
+                for (int p2 = 0; p2 < 2; ++p2) {
+                    float y[8];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float mine = act[4 * (2 * p2 + g) + i];            // group q = 2 p2 + g is mine
+                        const float send = act[4 * (2 * p2 + 1 - g) + i];        // the other lane half owns that group
+                        const float recv = __shfl_xor(send, 32, 64);
+                        y[i] = g == 0 ? mine : recv;
+                        y[4 + i] = g == 0 ? recv : mine;
+                    }
+                    uint16_t hi[8], lo[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        hi[e] = f32_to_bf16_rne(y[e]);
+                        lo[e] = f32_to_bf16_rne(y[e] - bf16_to_f32(hi[e]));
+                    }
+                    const int m = (mt0 + mt) * 32 + (lane & 31), k8 = (x0 / 2) * 4 + 2 * p2 + g;
+                    Opk[packA_u4(m, k8, mt_total, 0)] = *reinterpret_cast<u32x4*>(hi);
+                    Opk[packA_u4(m, k8, mt_total, 1)] = *reinterpret_cast<u32x4*>(lo);
+                }
+            }
+        }
+        continue;
+    }
     // C^T accumulator layout of the 32x32 MFMA: register r of lane l holds
     //   weight row n = 8*(r/4) + 4*(l/32) + r%4 of the tile, activation row m = l%32.
     // The tile goes through LDS (each wave its own slice, two m-tiles at a time) so that the global
@@ -252,15 +299,19 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
     return p;
 }
 
-void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s) {
+// Opk != nullptr: fused gate/up projection with the SwiGLU epilogue (needs plan.nt == 2 and plan.split_k == 1).
+void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s,
+                 u32x4* Opk) {
     const int n_tiles = N / 32, ksteps = (K + 63) / 64 * 4, m_groups = (mt_total + MT - 1) / MT;     // K padded to whole chunks
     const size_t split_stride = (size_t)mt_total * 32 * N;
     const int tiles_x = (n_tiles + 4 * plan.nt - 1) / (4 * plan.nt);
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
-    if (plan.nt == 2)
-        gemm_kernel<2><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups);
+    if (Opk)
+        gemm_kernel<2, true><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, Opk);
+    else if (plan.nt == 2)
+        gemm_kernel<2, false><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, nullptr);
     else
-        gemm_kernel<1><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups);
+        gemm_kernel<1, false><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, nullptr);
 }
 
 // The destination is laid out for K padded to a multiple of 64 (whole chunks); the padding must be zero.
@@ -269,7 +320,7 @@ __global__ void tile_weights_kernel(const u32x4* __restrict__ src, int rows, int
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= (size_t)rows * k8s) return;
     int r = (int)(i / k8s), k8 = (int)(i % k8s);
-    int n = interleave ? (r / 64) * 128 + r % 64 + row0 : row0 + r;
+    int n = interleave ? (r / 32) * 64 + r % 32 + row0 : row0 + r;      // fused gate/up: 32 rows of one, 32 of the other
     dst[tileW_u4(n, k8, ksteps_pad)] = src[i];
 }
 
