@@ -30,6 +30,53 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 static __device__ __forceinline__ f16x8 as_f16x8(const u32x4& v) { return *reinterpret_cast<const f16x8*>(&v); }
 #define MFMA16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
 
+// One page of the online softmax for a lane's 32 scores (16 consecutive keys of each key tile, one query).
+// Scores arrive in the log2 domain (the queries were scaled by log2(e) / sqrt(hd) when they were written),
+// so the exponentials are single v_exp_f32.  Updates the running max / sum, rescales the output
+// accumulators when some lane's max moved, and returns P as two fp16 terms in B-fragment order
+// (fragment kk = 2 kt + h: slot j of lane group g holds key 32 kt + 16 g + 8 h + j).
+template <int DT>
+static __device__ __forceinline__ void softmax_page(f32x16 (&s)[2], bool partial_page, int t0, int L, int g, float& m_run,
+                                                    float& l_run, f32x16 (&o)[DT], f16x8 (&ph)[4], f16x8 (&pl)[4]) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    if (partial_page) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                if (t0 + 32 * kt + 16 * g + r >= L) s[kt][r] = -INFINITY;
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kt][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);                           // finite: every page holds a valid key
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);      // 2^-inf = 0 on the first page
+    float sum = 0.f;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+        for (int r = 0; r < 16; r += 2) {
+            const f32x2 p = {__builtin_amdgcn_exp2f(s[kt][r] - m_new), __builtin_amdgcn_exp2f(s[kt][r + 1] - m_new)};
+            sum += p[0] + p[1];
+            const f16x2 hi = __builtin_convertvector(p, f16x2);
+            const f32x2 rem = p - __builtin_convertvector(hi, f32x2);
+            const f16x2 lo = __builtin_convertvector(rem, f16x2);
+            const int kk = 2 * kt + (r >> 3);
+            ph[kk][r & 7] = hi[0]; ph[kk][(r & 7) + 1] = hi[1];
+            pl[kk][r & 7] = lo[0]; pl[kk][(r & 7) + 1] = lo[1];
+        }
+    l_run = l_run * alpha + sum;
+    m_run = m_new;
+    if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+    }
+}
+
 template <int HD, bool SPLITQ>
 __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* __restrict__ Q, u32x4* __restrict__ Apk,
                                                         int layer, int mt_total, int seg_base, int n_splits,
@@ -51,7 +98,6 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* 
     const int tile_base = SPLITQ ? wg_base + 32 * wave : wg_base;     // this wave's 32 query rows
     const int kvh = blockIdx.y, seg_off = D.seg_off[gbr];
     const int L = D.hdr[gbr / D.max_br].L, n_pages = (L + BB_PAGE - 1) / BB_PAGE;
-    const float scale = 1.0f / sqrtf((float)HD);
 
     // Q fragments (B operand).  The contraction index may be enumerated in any order as long as K uses the
     // same one: k-step ks, lane group g, slot j  <->  head dim (HD/2) g + 8 ks + j, so a lane's KS fragments
@@ -115,36 +161,8 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* 
             fetch_half(kt, Vp);
             __builtin_amdgcn_sched_barrier(0);
         }
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = t0 + 32 * kt + 16 * g + r;
-                const float v = key < L ? s[kt][r] * scale : -INFINITY;
-                s[kt][r] = v;
-                mx = fmaxf(mx, v);
-            }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);               // finite: every page holds a valid key
-        const float alpha = expf(m_run - m_new);            // exp(-inf) = 0 on the first page
-        float sum = 0.f;
-        // P fragment kk = 2 kt + h (16 keys of the contraction): slot j of lane group g holds key 32 kt + 16 g + 8 h + j
         f16x8 ph[4], pl[4];
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float p = expf(s[kt][r] - m_new);
-                sum += p;
-                const _Float16 hi = (_Float16)p;
-                ph[2 * kt + (r >> 3)][r & 7] = hi;
-                pl[2 * kt + (r >> 3)][r & 7] = (_Float16)(p - (float)hi);
-            }
-        l_run = l_run * alpha + sum;
-        m_run = m_new;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+        softmax_page<DT>(s, t0 + BB_PAGE > L, t0, L, g, m_run, l_run, o, ph, pl);
         // fragment (dt, kk, term) = kv[(dt 4 + kk) 2 + term]
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
@@ -186,7 +204,7 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* 
             for (int w = 1; w < 4; ++w) M = fmaxf(M, sM[w][q]);
             float wgt[4], lsum = 0.f;
             for (int w = 0; w < 4; ++w) {
-                wgt[w] = sM[w][q] == -INFINITY ? 0.f : expf(sM[w][q] - M);
+                wgt[w] = sM[w][q] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sM[w][q] - M);   // maxima are in the log2 domain
                 lsum += wgt[w] * sL[w][q];
             }
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -214,7 +232,7 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* 
             for (int w = 1; w < 4; ++w) M = fmaxf(M, sM[w][q]);
             float wgt[4], lsum = 0.f;
             for (int w = 0; w < 4; ++w) {
-                wgt[w] = sM[w][q] == -INFINITY ? 0.f : expf(sM[w][q] - M);
+                wgt[w] = sM[w][q] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(sM[w][q] - M);   // maxima are in the log2 domain
                 lsum += wgt[w] * sL[w][q];
             }
             const float inv = 1.0f / lsum;
@@ -258,7 +276,7 @@ __global__ __launch_bounds__(256) void attention_combine_kernel(Dev D, const flo
         float lsum = 0.f, y[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         for (int s = 0; s < n_splits; ++s) {
             const float* ps = src + s * (64 + 32 * HD);
-            const float ms = ps[q], wgt = ms == -INFINITY ? 0.f : expf(ms - M);
+            const float ms = ps[q], wgt = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - M);
             lsum += wgt * ps[32 + q];
             const float4 a = *reinterpret_cast<const float4*>(ps + 64 + q * HD + d8 * 8);
             const float4 b = *reinterpret_cast<const float4*>(ps + 64 + q * HD + d8 * 8 + 4);

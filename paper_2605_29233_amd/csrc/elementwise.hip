@@ -172,6 +172,10 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
 #pragma unroll
         for (int e = 0; e < 4; ++e) { y1[e] = a1[e] * cc[e] - a2[e] * ss[e]; y2[e] = a2[e] * cc[e] + a1[e] * ss[e]; }
         if (ch < nq) {
+            // attention works with base-2 exponentials: fold log2(e) / sqrt(hd) into the queries
+            const float qs = 1.4426950408889634f / sqrtf((float)hd);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { y1[e] *= qs; y2[e] *= qs; }
             half_t* dst = Q + ((size_t)m * D.hq + ch / hd) * 2 * hd;
             put2x4(dst + j, dst + hd + j, y1);
             put2x4(dst + j + half, dst + hd + j + half, y2);
