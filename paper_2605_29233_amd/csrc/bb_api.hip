@@ -92,6 +92,7 @@ static int check_cfg(const bb_model_cfg* m, const bb_limits* l, std::string* why
     if (m->head_dim != 64 && m->head_dim != 128) return bad("head_dim must be 64 or 128");
     if (m->n_q_heads % m->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
     if (m->d_model % 64 || m->d_ffn % 16) return bad("d_model must be a multiple of 64 and d_ffn of 16");
+    if (m->d_model > 8192) return bad("d_model must not exceed 8192");
     if (m->d_model % 32 || (2 * m->d_ffn) % 32 || m->vocab % 32) return bad("projection row counts must be multiples of 32");
     if ((m->n_q_heads * m->head_dim) % 128 || (m->n_kv_heads * m->head_dim) % 128) return bad("q and kv widths must be multiples of 128");
     if (m->mask_id < 0 || m->mask_id >= m->vocab) return bad("mask_id out of range");
@@ -140,6 +141,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.seg_off = b.take<int>(nbr); D.seg_rows = b.take<int>(nbr);
     D.lm_row = b.take<int>(lm_pad);
     D.out_pred = b.take<int>(lm_pad); D.out_conf = b.take<float>(lm_pad); D.out_lse = b.take<float>(lm_pad);
+    D.vr_part = b.take<float4>((size_t)lm_pad * 8);
     D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
     D.req_list = b.take<int>(l.max_requests);
     c->d_stats = b.take<char>(sizeof(ReqHeader) + sizeof(bb_branch_state) * BB_MAX_BRANCHES);

@@ -56,6 +56,7 @@ struct Dev {
     int* seg_off; int* seg_rows;    // [max_req*max_br] packed rows of each branch (0 = inactive)
     int* lm_row;                // [lm_cap]
     int* out_pred; float* out_conf; float* out_lse;   // [lm_cap]
+    float4* vr_part;            // [lm_cap][8] per-segment (max, sum, argmax) of the vocabulary reduction
     PageCopy* copies;           // [max_req*max_br*n_pages]
     int* req_list;              // [max_req] request slots of the current call
 };

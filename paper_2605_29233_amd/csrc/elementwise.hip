@@ -63,6 +63,27 @@ static __device__ __forceinline__ float4 part_sum4(const float* __restrict__ P, 
     return v;
 }
 
+// The same for N offsets at once: the loads of a batch (4 splits x N offsets) are all issued before the
+// first add, so a thread pays the memory latency once per batch and not once per offset.
+template <int N>
+static __device__ __forceinline__ void part_sum4n(const float* __restrict__ P, int n_split, size_t stride, const size_t (&off)[N],
+                                                  float4 (&out)[N]) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) out[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < n_split; s += 4) {
+        float4 p[4][N];
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < N; ++i)
+                p[u][i] = s + u < n_split ? *reinterpret_cast<const float4*>(&P[(s + u) * stride + off[i]]) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < N; ++i) { out[i].x += p[u][i].x; out[i].y += p[u][i].y; out[i].z += p[u][i].z; out[i].w += p[u][i].w; }
+    }
+}
+
 // One workgroup per destination row j of the packed panel.  Source row r = j, or the j-th
 // masked row when gather != 0 (LM-head panel).  h[r] += sum_s partial[s][r] first (the residual
 // add of the preceding O / down projection), then y = h / sqrt(mean(h^2) + eps) * gain.
@@ -79,17 +100,31 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restr
     if (j >= count) { zero_packed_row(Apk, j, k8s, mt_total); return; }
     const int r = gather ? D.lm_row[j] : j;
     float* hr = h + (size_t)r * d;
+    // the row stays in registers between the two passes: thread t owns the 8-column groups t, t + 256, ...
+    constexpr int MAXG = 4;             // d <= 8192
+    float v[MAXG][8];
     float ss = 0.f;
-    for (int k4 = threadIdx.x; k4 < (d >> 2); k4 += blockDim.x) {
-        float4 v = reinterpret_cast<float4*>(hr)[k4];
-        if (n_partial) {
-            const float4 p = part_sum4(partial, n_partial, partial_stride, (size_t)r * d + k4 * 4);
-            v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
-            reinterpret_cast<float4*>(hr)[k4] = v;
+#pragma unroll
+    for (int i = 0; i < MAXG; ++i) {
+        const int k8 = threadIdx.x + 256 * i;
+        if (k8 < k8s) {
+            const float4 a = reinterpret_cast<const float4*>(hr)[2 * k8], b = reinterpret_cast<const float4*>(hr)[2 * k8 + 1];
+            float4 p[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
+            if (n_partial) {
+                const size_t off[2] = {(size_t)r * d + k8 * 8, (size_t)r * d + k8 * 8 + 4};
+                part_sum4n<2>(partial, n_partial, partial_stride, off, p);
+            }
+            v[i][0] = a.x + p[0].x; v[i][1] = a.y + p[0].y; v[i][2] = a.z + p[0].z; v[i][3] = a.w + p[0].w;
+            v[i][4] = b.x + p[1].x; v[i][5] = b.y + p[1].y; v[i][6] = b.z + p[1].z; v[i][7] = b.w + p[1].w;
+            if (n_partial) {
+                reinterpret_cast<float4*>(hr)[2 * k8] = make_float4(v[i][0], v[i][1], v[i][2], v[i][3]);
+                reinterpret_cast<float4*>(hr)[2 * k8 + 1] = make_float4(v[i][4], v[i][5], v[i][6], v[i][7]);
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) ss += v[i][q] * v[i][q];
         }
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
-    ss = wg_sum(ss, sh);            // also orders the writes to hr before the reads below
+    ss = wg_sum(ss, sh);
     const float inv = 1.0f / sqrtf(ss / (float)d + D.rms_eps);
     int gbr = 0, nb = 1; size_t mrow = 0;
     if (gather) {
@@ -99,16 +134,21 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restr
         if (bcast) { gbr = slot * D.max_br; nb = D.hdr[slot].N; }
         mrow = (size_t)gbr * D.gmax + gi;
     }
-    for (int k8 = threadIdx.x; k8 < k8s; k8 += blockDim.x) {
+#pragma unroll
+    for (int i = 0; i < MAXG; ++i) {
+        const int k8 = threadIdx.x + 256 * i;
+        if (k8 >= k8s) break;
+        const float4 g0 = reinterpret_cast<const float4*>(gain)[2 * k8], g1 = reinterpret_cast<const float4*>(gain)[2 * k8 + 1];
+        const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
         float y[8];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) y[q] = hr[k8 * 8 + q] * inv * gain[k8 * 8 + q];
+        for (int q = 0; q < 8; ++q) y[q] = v[i][q] * inv * gg[q];
         store_split(Apk, j, k8, mt_total, y);
         if (gather)
             for (int b = 0; b < nb; ++b) {
                 float* dst = D.map_hf + (mrow + (size_t)b * D.gmax) * d + k8 * 8;
-#pragma unroll
-                for (int q = 0; q < 8; ++q) dst[q] = y[q];
+                reinterpret_cast<float4*>(dst)[0] = make_float4(y[0], y[1], y[2], y[3]);
+                reinterpret_cast<float4*>(dst)[1] = make_float4(y[4], y[5], y[6], y[7]);
             }
     }
 }
@@ -155,17 +195,19 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
         const int hh = (t % per_row) / (half >> 2), j = ((t % per_row) % (half >> 2)) * 4;
         const int ch = c0 + hh * hd;                   // first column of this head
         const size_t off = (size_t)m * D.nqkv + ch + j;
-        float4 x1 = part_sum4(qkv, n_partial, partial_stride, off);
-        float4 x2 = part_sum4(qkv, n_partial, partial_stride, off + half);
+        const int pos = D.row_pos[m], phys = D.row_phys[m];
+        const float4 c = *reinterpret_cast<const float4*>(&D.rope_cos[(size_t)pos * half + j]);
+        const float4 sn = *reinterpret_cast<const float4*>(&D.rope_sin[(size_t)pos * half + j]);
+        const size_t offs[2] = {off, off + half};
+        float4 xs[2];
+        part_sum4n<2>(qkv, n_partial, partial_stride, offs, xs);
+        float4 x1 = xs[0], x2 = xs[1];
         if (bias) {
             const float4 b1 = *reinterpret_cast<const float4*>(&bias[ch + j]);
             const float4 b2 = *reinterpret_cast<const float4*>(&bias[ch + j + half]);
             x1.x += b1.x; x1.y += b1.y; x1.z += b1.z; x1.w += b1.w;
             x2.x += b2.x; x2.y += b2.y; x2.z += b2.z; x2.w += b2.w;
         }
-        const int pos = D.row_pos[m];
-        const float4 c = *reinterpret_cast<const float4*>(&D.rope_cos[(size_t)pos * half + j]);
-        const float4 sn = *reinterpret_cast<const float4*>(&D.rope_sin[(size_t)pos * half + j]);
         const float a1[4] = {x1.x, x1.y, x1.z, x1.w}, a2[4] = {x2.x, x2.y, x2.z, x2.w};
         const float cc[4] = {c.x, c.y, c.z, c.w}, ss[4] = {sn.x, sn.y, sn.z, sn.w};
         float y1[4], y2[4];
@@ -180,7 +222,7 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
             put2x4(dst + j, dst + hd + j, y1);
             put2x4(dst + j + half, dst + hd + j + half, y2);
         } else {
-            half_t* blk = D.Kc + kv_block_off(D, layer, D.row_phys[m], pos / BB_PAGE, (ch - nq) / hd);
+            half_t* blk = D.Kc + kv_block_off(D, layer, phys, pos / BB_PAGE, (ch - nq) / hd);
             const int tt = pos % BB_PAGE;
             put2x4(blk + k_slot(tt, j, 0, hd), blk + k_slot(tt, j, 1, hd), y1);
             put2x4(blk + k_slot(tt, j + half, 0, hd), blk + k_slot(tt, j + half, 1, hd), y2);
@@ -192,8 +234,10 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
         const int r = t / 16, cg = (t % 16) * 8, m = m0 + r;
         if (m < count) {
             const size_t off = (size_t)m * D.nqkv + c0 + cg;
-            float4 v0 = part_sum4(qkv, n_partial, partial_stride, off);
-            float4 v1 = part_sum4(qkv, n_partial, partial_stride, off + 4);
+            const size_t offs[2] = {off, off + 4};
+            float4 vs[2];
+            part_sum4n<2>(qkv, n_partial, partial_stride, offs, vs);
+            float4 v0 = vs[0], v1 = vs[1];
             if (bias) {
                 const float4 b0 = *reinterpret_cast<const float4*>(&bias[c0 + cg]);
                 const float4 b1 = *reinterpret_cast<const float4*>(&bias[c0 + cg + 4]);
@@ -236,8 +280,10 @@ __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float
         return;
     }
     const size_t off = (size_t)m * ldp + (f >> 5) * 64 + (f & 31);
-    const float4 g0 = part_sum4(gu, n_partial, partial_stride, off), g1 = part_sum4(gu, n_partial, partial_stride, off + 4);
-    const float4 u0 = part_sum4(gu, n_partial, partial_stride, off + 32), u1 = part_sum4(gu, n_partial, partial_stride, off + 36);
+    const size_t offs[4] = {off, off + 4, off + 32, off + 36};
+    float4 gs[4];
+    part_sum4n<4>(gu, n_partial, partial_stride, offs, gs);
+    const float4 g0 = gs[0], g1 = gs[1], u0 = gs[2], u1 = gs[3];
     const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
     const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
     float y[8];
@@ -267,13 +313,16 @@ static __device__ __forceinline__ MSI msi_merge(MSI a, MSI b) {
     return r;
 }
 
-__global__ __launch_bounds__(256) void vocab_reduce_kernel(Dev D, const float* __restrict__ logits, int bcast) {
+// Pass 1: workgroup (row j, segment) reduces its share of the row to (max, rescaled sum, argmax).
+#define VOCAB_SEGS 8
+__global__ __launch_bounds__(256) void vocab_reduce_kernel(Dev D, const float* __restrict__ logits) {
     __shared__ MSI sh[4];
-    const int j = blockIdx.x;
+    const int j = blockIdx.x, seg = blockIdx.y;
     if (j >= D.counts[1]) return;
     const float4* row = reinterpret_cast<const float4*>(logits + (size_t)j * D.vocab);
+    const int n4 = D.vocab >> 2, per = (n4 + VOCAB_SEGS - 1) / VOCAB_SEGS, lo = seg * per, hi = min(n4, lo + per);
     MSI a = {-INFINITY, 0.f, 0x7fffffff};
-    for (int v4 = threadIdx.x; v4 < (D.vocab >> 2); v4 += blockDim.x) {
+    for (int v4 = lo + threadIdx.x; v4 < hi; v4 += blockDim.x) {
         const float4 x4 = row[v4];
         const float xs[4] = {x4.x, x4.y, x4.z, x4.w};
 #pragma unroll
@@ -294,20 +343,35 @@ __global__ __launch_bounds__(256) void vocab_reduce_kernel(Dev D, const float* _
     if (threadIdx.x == 0) {
         MSI t = sh[0];
         for (int w = 1; w < 4; ++w) t = msi_merge(t, sh[w]);
-        const float conf = 1.0f / t.s, lse = t.m + logf(t.s);
-        D.out_pred[j] = t.i; D.out_conf[j] = conf; D.out_lse[j] = lse;
-        const int r = D.lm_row[j];
-        int gbr = D.row_gbr[r], nb = 1;
-        const int slot = gbr / D.max_br;
-        const int gi = D.row_pos[r] - D.hdr[slot].L_p;
-        if (bcast) { gbr = slot * D.max_br; nb = D.hdr[slot].N; }
-        for (int b = 0; b < nb; ++b) {
-            const size_t m = (size_t)(gbr + b) * D.gmax + gi;
-            D.map_pred[m] = t.i; D.map_conf[m] = conf; D.map_lse[m] = lse;
-        }
+        D.vr_part[(size_t)j * VOCAB_SEGS + seg] = make_float4(t.m, t.s, __int_as_float(t.i), 0.f);
+    }
+}
+
+// Pass 2: one thread per row merges the segments in order and writes confidence, token and lse, also into the
+// probability map of the row's branch (of every branch of the request after the initial forward).
+__global__ void vocab_finish_kernel(Dev D, int bcast) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= D.counts[1]) return;
+    MSI t = {-INFINITY, 0.f, 0x7fffffff};
+    for (int seg = 0; seg < VOCAB_SEGS; ++seg) {
+        const float4 p = D.vr_part[(size_t)j * VOCAB_SEGS + seg];
+        const MSI b = {p.x, p.y, __float_as_int(p.z)};
+        t = msi_merge(t, b);
+    }
+    const float conf = 1.0f / t.s, lse = t.m + logf(t.s);
+    D.out_pred[j] = t.i; D.out_conf[j] = conf; D.out_lse[j] = lse;
+    const int r = D.lm_row[j];
+    int gbr = D.row_gbr[r], nb = 1;
+    const int slot = gbr / D.max_br;
+    const int gi = D.row_pos[r] - D.hdr[slot].L_p;
+    if (bcast) { gbr = slot * D.max_br; nb = D.hdr[slot].N; }
+    for (int b = 0; b < nb; ++b) {
+        const size_t m = (size_t)(gbr + b) * D.gmax + gi;
+        D.map_pred[m] = t.i; D.map_conf[m] = conf; D.map_lse[m] = lse;
     }
 }
 
 void launch_vocab_reduce(const Dev& D, const float* logits, int lm_cap, int bcast, hipStream_t s) {
-    vocab_reduce_kernel<<<lm_cap, 256, 0, s>>>(D, logits, bcast);
+    vocab_reduce_kernel<<<dim3(lm_cap, VOCAB_SEGS), 256, 0, s>>>(D, logits);
+    vocab_finish_kernel<<<(lm_cap + 63) / 64, 64, 0, s>>>(D, bcast);
 }
