@@ -30,7 +30,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+                    help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (every box has one); --gpus must be 1", file=sys.stderr)
@@ -139,15 +139,17 @@ def main():
                      "traffic": None, "avg_launch_ms": gemm_ms, "launches": g["launches"],
                      "mfma_tflops": gemm_tflops, "mfma_frac_of_bf16_peak": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
     }
+    if args.copy_calibration:
+        # one plain copy of known size (256 MiB in, 256 MiB out, 16 bytes per lane like the library's kernels)
+        src = torch.ones(1 << 28, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        bb.debug_copy16(src, dst)
+        bb.synchronize()
+        assert bool((dst == 1).all())
+        del src, dst
     bb.close()
     del bb
     torch.cuda.empty_cache()
-    if args.copy_calibration:
-        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
 
     # ---- 5. the CPU oracle on the host cores (reported baseline, bounded sample) ----------------------
     if not args.no_cpu_baseline:

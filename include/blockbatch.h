@@ -205,6 +205,12 @@ int bb_debug_gemm(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, floa
  * panels of at most 128 rows.  Results are unchanged up to fp32 summation order. */
 int bb_debug_set_gemm_plan(bb_ctx* ctx, int kind, int nt, int split_k);
 
+/* Measurement aid: copy `bytes` (a multiple of 16) from src_dev to dst_dev (device pointers, disjoint,
+ * 16-byte aligned) on the context's stream with a plain kernel that moves 16 bytes per lane, the access
+ * width of the library's kernels.  A known-size reference for scaling hardware traffic counters, whose
+ * reading per byte depends on the request size.  Asynchronous; BB_EINVAL on misaligned arguments. */
+int bb_debug_copy16(bb_ctx* ctx, const void* src_dev, void* dst_dev, size_t bytes);
+
 #ifdef __cplusplus
 }
 #endif

@@ -63,7 +63,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -103,6 +103,7 @@ def load_library():
         lib.bb_profile_enable.argtypes = [C.c_void_p, C.c_int]
         lib.bb_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]
         lib.bb_debug_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
+        lib.bb_debug_copy16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         _LIB = lib
     return _LIB
 
@@ -245,7 +246,7 @@ class BlockBatch:
         self._chk(self.lib.bb_synchronize(self._ctx), "bb_synchronize")
 
     def set_gemm_plan(self, kind, nt, split_k):
-        self._chk(self.lib.bb_debug_set_gemm_plan(self._ctx, kind, nt, split_k), "bb_debug_set_gemm_plan")
+        self._chk(self.lib.bb_debug_set_gemm_plan(self._ctx, kind, nt, split_k), "bb_debug_set_gemm_plan", "bb_debug_copy16")
 
     def profile_enable(self, on=True):
         self._chk(self.lib.bb_profile_enable(self._ctx, int(on)), "bb_profile_enable")
@@ -285,6 +286,13 @@ class BlockBatch:
         V = np.empty(shp, dtype=np.float32)
         self._chk(self.lib.bb_get_kv(self._ctx, rid, branch, layer, K.ctypes.data_as(C.c_void_p), V.ctypes.data_as(C.c_void_p)), "bb_get_kv")
         return K, V
+
+    def debug_copy16(self, src, dst):
+        """Plain 16-byte-per-lane device copy of one torch tensor into another (traffic-counter reference)."""
+        assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+        nbytes = src.numel() * src.element_size()
+        assert nbytes == dst.numel() * dst.element_size()
+        self._chk(self.lib.bb_debug_copy16(self._ctx, C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), nbytes), "bb_debug_copy16")
 
     def debug_gemm(self, A, W_bits, split_k=0):
         A = np.ascontiguousarray(A, dtype=np.float32)

@@ -644,3 +644,18 @@ extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float
         }
     return BB_OK;
 }
+
+// ---- traffic-counter reference ----------------------------------------------------------------------
+__global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+extern "C" int bb_debug_copy16(bb_ctx* c, const void* src_dev, void* dst_dev, size_t bytes) {
+    if (!c || !src_dev || !dst_dev) return BB_EINVAL;
+    if (bytes % 16 || (uintptr_t)src_dev % 16 || (uintptr_t)dst_dev % 16) return fail(c, BB_EINVAL, "bb_debug_copy16: arguments must be multiples of 16");
+    if (bytes == 0) return BB_OK;
+    const size_t n = bytes / 16;
+    copy16_kernel<<<(unsigned)std::min<size_t>((n + 255) / 256, 16384), 256, 0, c->stream>>>((const u32x4*)src_dev, (u32x4*)dst_dev, n);
+    HIPCHK(c, hipGetLastError());
+    return BB_OK;
+}

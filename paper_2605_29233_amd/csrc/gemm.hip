@@ -59,12 +59,24 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // a workgroup walks the (column group, row group) tiles with the grid's stride: at most one round of
     // workgroups is ever launched, the rest of the tiles are taken by the same workgroups
-    for (int tile = blockIdx.x; tile < tiles_x * tiles_y; tile += gridDim.x) {
+    //
+    // Workgroups go to the 8 XCDs (each with its own L2) round robin by linear id.  With a k split the
+    // (column group, split) items are dealt out so that an XCD gets a contiguous run of them in split-major
+    // order: its workgroups then share one or two k ranges of the activation panel, which its L2 fetches
+    // once, instead of every XCD fetching the whole panel.
+    int first_tile = blockIdx.x, split_id = blockIdx.z;
+    if (gridDim.z > 1 && tiles_y == 1) {
+        const int n = gridDim.x * gridDim.z, lin = blockIdx.x + gridDim.x * blockIdx.z, e = lin & 7;
+        const int item = e * (n >> 3) + min(e, n & 7) + (lin >> 3);
+        first_tile = item % gridDim.x;
+        split_id = item / gridDim.x;
+    }
+    for (int tile = first_tile; tile < tiles_x * tiles_y; tile += gridDim.x) {
     const int bx = tile % tiles_x, by = tile / tiles_x;
     const int mt0 = by * MT;
     const int mt_cnt = min(MT, mt_total - mt0);
     const int total_chunks = ksteps / KC;
-    const int c0 = blockIdx.z * chunks_per_split;
+    const int c0 = split_id * chunks_per_split;
     const int c1 = min(c0 + chunks_per_split, total_chunks);
     if (c0 >= c1) continue;
 
@@ -237,7 +249,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     constexpr int COLS = 32 * NT, LDT = COLS + 4;          // row stride in floats (16-byte aligned, conflict-free)
     __syncthreads();                                        // all waves are done with the staged activations
     float* tl = reinterpret_cast<float*>(&lds[0][0]) + wave * (64 * LDT);
-    float* Ps = P + (size_t)blockIdx.z * split_stride;
+    float* Ps = P + (size_t)split_id * split_stride;
     const int x0 = (bx * 4 + wave) * NT;                    // first weight tile of this wave
 #pragma unroll
     for (int half = 0; half < 2; ++half) {

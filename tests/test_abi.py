@@ -22,7 +22,7 @@ def lib():
 
 def test_exports_every_declared_symbol(lib):
     hdr = open(os.path.join(ROOT, "include", "blockbatch.h")).read()
-    declared = set(re.findall(r"\b(bb_[a-z_]+)\s*\(", hdr))
+    declared = set(re.findall(r"\b(bb_[a-z0-9_]+)\s*\(", hdr))
     assert {"bb_load_weights", "bb_refresh", "bb_denoise_step", "bb_merge_commit"} <= declared
     for name in declared:
         assert hasattr(lib, name), f"{name} is declared in blockbatch.h but not exported"
