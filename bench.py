@@ -21,6 +21,13 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
+# HBM bytes per GEMM launch of a block forward from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled
+# by what the counter reads for a plain 16-byte-per-lane copy of known size (FETCH_SIZE x 2.000, WRITE_SIZE x
+# 1.000); the per-kernel table and the commands are in profiles/llada_hbm_traffic_pmc.md.  Counters cannot be
+# read from inside this process, so the figure is the stored one for the workload it was measured on.
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"llada": 150.7e6}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -136,7 +143,9 @@ def main():
         "kernel_ms_per_block_forward": per_step,
         "roofline": {"bound": "hbm", "kernel": "gemm_kernel (weight-streaming MFMA GEMM, block forward)",
                      "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "avg_launch_ms": gemm_ms, "launches": g["launches"],
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(w.name), "traffic_unit": "bytes/launch",
+                     "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1),
+                     "avg_launch_ms": gemm_ms, "launches": g["launches"],
                      "mfma_tflops": gemm_tflops, "mfma_frac_of_bf16_peak": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
     }
     if args.copy_calibration:
