@@ -61,6 +61,8 @@ def test_tiny_full_trajectory():
     (3, (16, 16, 16), 64, 48, DecodeParams(0.9, 0.5, 8, 4, 1)),        # equal block sizes
     (4, (64,), 40, 64, DecodeParams(1.5, 0.5, 8, 1, 0)),               # one block = whole generation, R = 1
     (5, (4, 8, 16, 32, 64), 100, 128, DecodeParams(0.9, 0.5, 8, 8, 0)),
+    (6, (4, 8, 16, 32, 64, 128), 90, 256, DecodeParams(0.9, 0.5, 8, 32, 0)),   # the paper's six-branch setting (App. E.3)
+    (7, (32,), 64, 96, DecodeParams(0.9, 0.5, 8, 8, 0)),               # one branch, one block size
 ])
 def test_tiny_variants(seed, blocks, prompt_len, gen_len, decode):
     w = workload("tiny")

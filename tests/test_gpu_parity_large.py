@@ -69,6 +69,11 @@ def test_llada_long_context():
     single_request("llada_long", steps=1)
 
 
+def test_llada_paper_six_branches():
+    """Six branches of block sizes 4..128 (App. E.3): 252 packed rows, two row groups in the skinny GEMMs."""
+    single_request("llada_paper6", steps=2)
+
+
 def test_llada_16_requests_sampled():
     """All 16 requests run batched on the GPU; the oracle follows two of them."""
     w, bb, om = setup("llada_x16")

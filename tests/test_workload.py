@@ -2,7 +2,7 @@
 import numpy as np
 import torch
 
-from workload import workload, gen_weights, gen_prompt, weight_specs, WORKLOAD_NAMES
+from workload import workload, gen_weights, gen_prompt, weight_specs, WORKLOAD_NAMES, EXTRA_WORKLOAD_NAMES
 from workload.gen import gen_normal_bf16, gen_tensor
 
 
@@ -42,7 +42,7 @@ def test_lm_head_scale_rule():
 
 
 def test_prompts_exclude_mask_and_lengths():
-    for name in WORKLOAD_NAMES:
+    for name in WORKLOAD_NAMES + EXTRA_WORKLOAD_NAMES:
         w = workload(name)
         for r, lp in enumerate(w.prompt_lens):
             p = gen_prompt(w.model, w.seed, r, lp)

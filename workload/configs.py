@@ -63,10 +63,13 @@ LLADA = ModelShape("llada8b", 32, 4096, 32, 32, 128, 12288, 126464)
 DREAM = ModelShape("dream7b", 28, 3584, 28, 4, 128, 18944, 152064, qkv_bias=True)
 
 WORKLOAD_NAMES = ("tiny", "llada", "dream", "llada_x16", "llada_long")
+# further settings run through the same path: the paper's main six-branch setting (App. E.3) and the
+# single-branch special cases that stand for its baselines (one block size with a KV cache; no cache)
+EXTRA_WORKLOAD_NAMES = ("llada_paper6", "llada_b32", "llada_vanilla")
 
 
 def workload(name: str) -> Workload:
-    """Return one of the five named workloads (prompt lengths of llada_x16 come from gen.py)."""
+    """Return a named workload (prompt lengths of llada_x16 come from gen.py)."""
     if name == "tiny":
         return Workload("tiny", TINY, DecodeParams(refresh_interval=4, leader_rule=1), 64, (8, 16, 32), (64,))
     if name == "llada":
@@ -79,6 +82,12 @@ def workload(name: str) -> Workload:
         return Workload("llada_x16", LLADA, DecodeParams(refresh_interval=8), 256, (8, 16, 32, 64), lens)
     if name == "llada_long":
         return Workload("llada_long", LLADA, DecodeParams(refresh_interval=16), 1024, (16, 32, 64, 128), (4096,))
+    if name == "llada_paper6":      # six branches 4..128, tau_sync 8, R 32, tau_merge 0.5: 252 packed rows per step
+        return Workload("llada_paper6", LLADA, DecodeParams(refresh_interval=32), 256, (4, 8, 16, 32, 64, 128), (512,))
+    if name == "llada_b32":         # one branch, block 32, cached KV refreshed every 8 forwards
+        return Workload("llada_b32", LLADA, DecodeParams(refresh_interval=8), 256, (32,), (512,))
+    if name == "llada_vanilla":     # one block = the whole generation, refresh after every forward, one token per step
+        return Workload("llada_vanilla", LLADA, DecodeParams(tau_dec=1.5, refresh_interval=1), 256, (256,), (512,))
     raise KeyError(name)
 
 
