@@ -16,7 +16,8 @@ from dataclasses import dataclass, field
 import numpy as np
 
 from .model import OracleModel, softmax_rows, confidence_argmax
-from .policy import (Branch, decode_current_block, advance_block, merge_sync, tokens_decoded)
+from .policy import (Branch, decode_current_block, advance_block, merge_sync, tokens_decoded, check_eos,
+                     select_winner)
 
 
 @dataclass
@@ -51,6 +52,10 @@ class OracleRequest:
         self.nfe = {"init": 0, "block": 0, "refresh": 0}
         self.pending = None       # ForwardResult awaiting commit_merge
         self.refresh_due = False
+        self.eos_id = getattr(params, "eos_id", -1)
+        self.finished = 0         # 1: every branch done; 2: an EOS-ready branch was selected
+        self.winner = -1
+        self.eos_pos = -1
 
     # ---- forwards ---------------------------------------------------------------
     def _result(self, branch, pos, hidden, window_rows):
@@ -147,10 +152,26 @@ class OracleRequest:
         """DecodeCurrentBlock + UpdateProbabilityMap per branch, AdvanceCompletedBlocks,
         MergeSync, and the refresh cadence (a refresh is due once R block forwards have run
         since the last one).  Returns a dict of what happened."""
+        decoded_now = sorted(set(int(k) for k in self.pending.branch)) if self.pending is not None else []
+        decoded_now = [k for k in decoded_now if not self.br[k].done]
         commits = self.decode_all()
+        # CheckEOS for the branches that were just decoded; an EOS-ready branch ends the request
+        ready = [k for k in decoded_now if check_eos(self.X, k, self.L_p, self.eos_id, self.mask_id)[1]]
+        if ready:
+            self.winner = select_winner(self.X, ready, self.L_p, self.mask_id)
+            self.eos_pos = check_eos(self.X, self.winner, self.L_p, self.eos_id, self.mask_id)[0]
+            self.finished = 2
+            for br in self.br:
+                br.done, br.start, br.end = True, self.L, self.L
+            self.refresh_due = False
+            return {"commits": commits, "merges": [], "syncs": [], "refresh_due": False}
         self.advance_all()
         merges, syncs = self.merge_sync_all()
         self.refresh_due = self.since_refresh >= self.p.refresh_interval and any(not b.done for b in self.br)
+        if self.all_done():
+            self.finished = 1
+            self.winner = select_winner(self.X, range(self.N), self.L_p, self.mask_id)
+            self.eos_pos = check_eos(self.X, self.winner, self.L_p, self.eos_id, self.mask_id)[0]
         return {"commits": commits, "merges": merges, "syncs": syncs, "refresh_due": self.refresh_due}
 
     # ---- convenience ------------------------------------------------------------
@@ -161,8 +182,8 @@ class OracleRequest:
         return [tokens_decoded(self.X, k, self.L_p, self.mask_id) for k in range(self.N)]
 
     def run(self, max_steps=100000):
-        """Alg. 1 to completion (no EOS handling).  Returns the row of the branch with the most
-        progress (lowest index on ties)."""
+        """Alg. 1 to completion: returns the row of the EOS winner if an EOS-ready branch appears,
+        else of the branch with the most progress (lowest index on ties)."""
         self.init_forward()
         self.commit_merge()
         if self.refresh_due:
@@ -174,5 +195,7 @@ class OracleRequest:
             if self.refresh_due:
                 self.refresh()
             steps += 1
+        if self.finished:
+            return self.X[self.winner].copy()
         prog = self.progress()
         return self.X[int(np.argmax(prog))].copy()

@@ -85,6 +85,26 @@ def pick_leader(X, branches, L_p, mask_id, leader_rule):
     return min(branches, key=key)
 
 
+def check_eos(X, k, L_p, eos_id, mask_id):
+    """CheckEOS of Alg. 1 (and the EOS cycle of Fig. 5's caption), read on the token row alone: the
+    branch's EOS is the first generation position that holds the EOS token; the branch is
+    EOS-ready when no position between the prompt and that EOS is still masked, otherwise it
+    stays in the EOS cycle, i.e. it simply keeps decoding.  Returns (eos position or -1, ready)."""
+    if eos_id < 0:
+        return -1, False
+    hits = np.nonzero(X[k, L_p:] == eos_id)[0]
+    if len(hits) == 0:
+        return -1, False
+    e = L_p + int(hits[0])
+    return e, not bool(np.any(X[k, L_p:e] == mask_id))
+
+
+def select_winner(X, candidates, L_p, mask_id):
+    """SelectEOSWinner among the EOS-ready branches, and the final selection of Alg. 1 among all
+    branches: most progress (tokens decoded), lowest index on ties."""
+    return min(candidates, key=lambda k: (-tokens_decoded(X, k, L_p, mask_id), k))
+
+
 def compatible(X, s, d, mask_id):
     """Sec. 4.1: every position decoded in both rows holds the same token."""
     both = (X[s] != mask_id) & (X[d] != mask_id)

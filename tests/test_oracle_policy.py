@@ -244,3 +244,65 @@ def test_realign_window():
     X[0, 5] = 1
     realign_window(X, br, 2, 10, M)
     assert (br.start, br.end) == (6, 10)
+
+
+# ---- CheckEOS / SelectEOSWinner / final selection (Alg. 1) --------------------------------------
+def test_check_eos_hand_cases():
+    from oracle.policy import check_eos
+    E = 7
+    X = np.array([
+        [1, 2, 5, E, M, 6],       # EOS at 3, prefix (position 2) decoded -> ready
+        [1, 2, M, E, 4, 6],       # EOS at 3 but position 2 masked -> EOS cycle, not ready
+        [1, 2, 5, 4, M, 6],       # no EOS
+        [1, 2, E, M, E, 6],       # two EOS: the first counts, empty prefix -> ready
+        [E, 2, 5, M, M, E],       # EOS in the prompt does not count; generation EOS at 5 with masks before
+    ])
+    assert check_eos(X, 0, 2, E, M) == (3, True)
+    assert check_eos(X, 1, 2, E, M) == (3, False)
+    assert check_eos(X, 2, 2, E, M) == (-1, False)
+    assert check_eos(X, 3, 2, E, M) == (2, True)
+    assert check_eos(X, 4, 2, E, M) == (5, False)
+    assert check_eos(X, 0, 2, -1, M) == (-1, False)          # disabled
+    X[1, 2] = 9                                               # the cycle ends once the prefix is contiguous
+    assert check_eos(X, 1, 2, E, M) == (3, True)
+
+
+def test_select_winner_most_progress_then_lowest_index():
+    from oracle.policy import select_winner
+    X = np.array([[1, 5, M, M], [1, 5, 6, M], [1, 8, 9, M], [1, M, M, M]])
+    assert select_winner(X, [0, 1, 2, 3], 1, M) == 1          # 2 decoded, tie between 1 and 2 -> lower index
+    assert select_winner(X, [2, 0], 1, M) == 2
+    assert select_winner(X, [3], 1, M) == 3
+
+
+def test_eos_run_matches_plain_run_until_it_stops(tiny):
+    """With an EOS id the trajectory is the plain one until some decoded branch is EOS-ready; the
+    request then ends with that branch's row: EOS present, nothing masked before it."""
+    import dataclasses
+    w, m, pr = tiny
+    plain = OracleRequest(m, pr, w.gen_len, w.block_sizes, w.decode)
+    hist = []
+    plain.init_forward(); plain.commit_merge(); hist.append(plain.X.copy())
+    while not plain.all_done():
+        if plain.refresh_due:
+            plain.refresh()
+        plain.block_forward(); plain.commit_merge(); hist.append(plain.X.copy())
+    assert plain.finished == 1 and plain.winner == 0 and plain.eos_pos == -1     # all rows complete: lowest index
+    final = plain.X[plain.winner]
+    # a token of the final text that does not occur earlier in it, a third of the way in
+    j = next(j for j in range(w.gen_len // 8, w.gen_len) if final[plain.L_p + j] not in final[plain.L_p:plain.L_p + j])
+    eos = int(final[plain.L_p + j])
+    rq = OracleRequest(m, pr, w.gen_len, w.block_sizes, dataclasses.replace(w.decode, eos_id=eos))
+    rq.init_forward(); rq.commit_merge()
+    n = 0
+    while not rq.finished:
+        assert np.array_equal(rq.X, hist[n])
+        if rq.refresh_due:
+            rq.refresh()
+        rq.block_forward(); rq.commit_merge(); n += 1
+    assert rq.finished == 2 and n <= len(hist) - 1
+    row = rq.X[rq.winner]
+    assert row[rq.eos_pos] == eos and eos not in row[rq.L_p:rq.eos_pos]
+    assert not np.any(row[rq.L_p:rq.eos_pos] == rq.mask_id)
+    assert rq.all_done() and not rq.refresh_due
+    # the step before, no decoded branch was ready

@@ -41,6 +41,7 @@ class DecodeParams:
     tau_sync: int = 8            # Alg. 2 sync gap (>)
     refresh_interval: int = 8    # R: block forwards between full-sequence refreshes
     leader_rule: int = 0         # 0: most tokens decoded (Alg. 2); 1: highest mean confidence
+    eos_id: int = -1             # end-of-sequence token of CheckEOS (Alg. 1); -1: no EOS handling
 
 
 @dataclass(frozen=True)
