@@ -66,6 +66,7 @@ typedef struct {
     int   tau_sync;         /* Alg. 2: copy the leader if its lead is      >  tau_sync      */
     int   refresh_interval; /* R: block forwards between full-sequence refreshes            */
     int   leader_rule;      /* 0: most tokens decoded (Alg. 2); 1: highest mean confidence  */
+    int   eos_id;           /* CheckEOS (Alg. 1): end-of-sequence token id, -1 = no EOS handling */
 } bb_decode_cfg;
 
 /* Capacity the workspace is sized for. */
@@ -122,6 +123,10 @@ typedef struct {
     int refresh_due;               /* R block forwards have run since the last refresh      */
     int all_done;
     int nfe_init, nfe_block, nfe_refresh;   /* one batched forward = one NFE (Sec. 5.1)      */
+    int finished;                  /* 0 running; 1 every branch done; 2 an EOS-ready branch was selected */
+    int winner;                    /* finished != 0: the branch whose row is the output (SelectEOSWinner, or
+                                      the final argmax-progress selection of Alg. 1); else -1          */
+    int eos_pos;                   /* absolute position of the winner's first EOS, -1 if it has none    */
     bb_branch_state branch[BB_MAX_BRANCHES];
 } bb_request_stats;
 
@@ -158,6 +163,15 @@ int bb_denoise_step(bb_ctx* ctx, const int* req_ids_host, int n, bb_step_view* v
  * stats_out_host (may be NULL): n entries; when given, the call waits for the stream and
  * copies the summaries to the host; when NULL the call is asynchronous. */
 int bb_merge_commit(bb_ctx* ctx, const int* req_ids_host, int n, bb_request_stats* stats_out_host);
+
+/* Alg. 1 from start to end for requests that were opened and not yet initialised: the initial full
+ * forward of each, then { block forward, commit / CheckEOS / merge / sync, refresh when due } over the
+ * requests still running, until every one has finished (all branches done, or an EOS-ready branch
+ * selected) or max_block_forwards batched forwards have run.  Reads each request's flags back after
+ * every commit (one small copy per step).  stats_out_host: n entries (may be NULL).  The output of
+ * request i is row stats[i].winner of bb_get_tokens, up to stats[i].eos_pos if that is >= 0.
+ * Returns BB_OK also when the forward limit stopped it (finished == 0 then). */
+int bb_generate(bb_ctx* ctx, const int* req_ids_host, int n, int max_block_forwards, bb_request_stats* stats_out_host);
 
 /* ---- inspection and teacher forcing (tests, harness); all synchronise the stream ---- */
 /* Device pointers to the results of the latest forward (what bb_denoise_step returns in

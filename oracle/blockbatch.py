@@ -152,27 +152,42 @@ class OracleRequest:
         """DecodeCurrentBlock + UpdateProbabilityMap per branch, AdvanceCompletedBlocks,
         MergeSync, and the refresh cadence (a refresh is due once R block forwards have run
         since the last one).  Returns a dict of what happened."""
-        decoded_now = sorted(set(int(k) for k in self.pending.branch)) if self.pending is not None else []
-        decoded_now = [k for k in decoded_now if not self.br[k].done]
+        decoded_now = self.decoded_branches()
         commits = self.decode_all()
-        # CheckEOS for the branches that were just decoded; an EOS-ready branch ends the request
-        ready = [k for k in decoded_now if check_eos(self.X, k, self.L_p, self.eos_id, self.mask_id)[1]]
-        if ready:
-            self.winner = select_winner(self.X, ready, self.L_p, self.mask_id)
-            self.eos_pos = check_eos(self.X, self.winner, self.L_p, self.eos_id, self.mask_id)[0]
-            self.finished = 2
-            for br in self.br:
-                br.done, br.start, br.end = True, self.L, self.L
-            self.refresh_due = False
+        if self.eos_finish(decoded_now):
             return {"commits": commits, "merges": [], "syncs": [], "refresh_due": False}
         self.advance_all()
         merges, syncs = self.merge_sync_all()
+        self.end_of_commit()
+        return {"commits": commits, "merges": merges, "syncs": syncs, "refresh_due": self.refresh_due}
+
+    def decoded_branches(self):
+        """Branches that DecodeCurrentBlock is about to run on (those CheckEOS looks at afterwards)."""
+        if self.pending is None:
+            return []
+        return [k for k in sorted(set(int(k) for k in self.pending.branch)) if not self.br[k].done]
+
+    def eos_finish(self, decoded_now):
+        """CheckEOS for the branches that were just decoded; an EOS-ready branch ends the request
+        (SelectEOSWinner), before AdvanceCompletedBlocks and MergeSync as in Alg. 1."""
+        ready = [k for k in decoded_now if check_eos(self.X, k, self.L_p, self.eos_id, self.mask_id)[1]]
+        if not ready:
+            return False
+        self.winner = select_winner(self.X, ready, self.L_p, self.mask_id)
+        self.eos_pos = check_eos(self.X, self.winner, self.L_p, self.eos_id, self.mask_id)[0]
+        self.finished = 2
+        for br in self.br:
+            br.done, br.start, br.end = True, self.L, self.L
+        self.refresh_due = False
+        return True
+
+    def end_of_commit(self):
+        """Refresh cadence, and the final selection once every branch is done."""
         self.refresh_due = self.since_refresh >= self.p.refresh_interval and any(not b.done for b in self.br)
-        if self.all_done():
+        if self.all_done() and not self.finished:
             self.finished = 1
             self.winner = select_winner(self.X, range(self.N), self.L_p, self.mask_id)
             self.eos_pos = check_eos(self.X, self.winner, self.L_p, self.eos_id, self.mask_id)[0]
-        return {"commits": commits, "merges": merges, "syncs": syncs, "refresh_due": self.refresh_due}
 
     # ---- convenience ------------------------------------------------------------
     def all_done(self):

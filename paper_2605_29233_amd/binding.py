@@ -21,7 +21,7 @@ class bb_model_cfg(C.Structure):
 
 class bb_decode_cfg(C.Structure):
     _fields_ = [("tau_dec", C.c_float), ("tau_merge", C.c_float), ("tau_sync", C.c_int),
-                ("refresh_interval", C.c_int), ("leader_rule", C.c_int)]
+                ("refresh_interval", C.c_int), ("leader_rule", C.c_int), ("eos_id", C.c_int)]
 
 
 class bb_limits(C.Structure):
@@ -38,7 +38,8 @@ class BranchState(C.Structure):
 
 
 class RequestStats(C.Structure):
-    _fields_ = [(n, C.c_int) for n in ("n_branches", "refresh_due", "all_done", "nfe_init", "nfe_block", "nfe_refresh")] + \
+    _fields_ = [(n, C.c_int) for n in ("n_branches", "refresh_due", "all_done", "nfe_init", "nfe_block", "nfe_refresh",
+                                             "finished", "winner", "eos_pos")] + \
                [("branch", BranchState * BB_MAX_BRANCHES)]
 
 
@@ -63,7 +64,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -103,6 +104,7 @@ def load_library():
         lib.bb_profile_enable.argtypes = [C.c_void_p, C.c_int]
         lib.bb_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]
         lib.bb_debug_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
+        lib.bb_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         lib.bb_debug_copy16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         _LIB = lib
     return _LIB
@@ -145,7 +147,8 @@ class BlockBatch:
         self.model, self.decode, self.limits = model, decode, limits
         self._mc = bb_model_cfg(model.n_layers, model.d_model, model.n_q_heads, model.n_kv_heads, model.head_dim,
                                 model.d_ffn, model.vocab, model.rope_base, model.rms_eps, int(model.qkv_bias), model.mask_id)
-        self._dc = bb_decode_cfg(decode.tau_dec, decode.tau_merge, decode.tau_sync, decode.refresh_interval, decode.leader_rule)
+        self._dc = bb_decode_cfg(decode.tau_dec, decode.tau_merge, decode.tau_sync, decode.refresh_interval, decode.leader_rule,
+                                 getattr(decode, "eos_id", -1))
         self._lim = bb_limits(limits.max_requests, limits.max_branches, limits.max_seq_len, limits.max_gen_len, limits.max_step_rows)
         nbytes = self.lib.bb_workspace_bytes(C.byref(self._mc), C.byref(self._lim))
         if nbytes == 0:
@@ -241,12 +244,19 @@ class BlockBatch:
         self._chk(self.lib.bb_merge_commit(self._ctx, p, n, C.cast(st, C.c_void_p)), "bb_merge_commit")
         return list(st)
 
+    def generate(self, ids, max_block_forwards=1 << 30):
+        """Alg. 1 from the initial forward to the end for opened, uninitialised requests; returns their stats."""
+        a, p, n = self._ids(ids)
+        st = (RequestStats * n)()
+        self._chk(self.lib.bb_generate(self._ctx, p, n, int(max_block_forwards), C.cast(st, C.c_void_p)), "bb_generate")
+        return list(st)
+
     # -- inspection ---------------------------------------------------------------------------
     def synchronize(self):
         self._chk(self.lib.bb_synchronize(self._ctx), "bb_synchronize")
 
     def set_gemm_plan(self, kind, nt, split_k):
-        self._chk(self.lib.bb_debug_set_gemm_plan(self._ctx, kind, nt, split_k), "bb_debug_set_gemm_plan", "bb_debug_copy16")
+        self._chk(self.lib.bb_debug_set_gemm_plan(self._ctx, kind, nt, split_k), "bb_debug_set_gemm_plan")
 
     def profile_enable(self, on=True):
         self._chk(self.lib.bb_profile_enable(self._ctx, int(on)), "bb_profile_enable")

@@ -120,7 +120,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.f = m.d_ffn; D.vocab = m.vocab; D.mask_id = m.mask_id; D.qkv_bias = m.qkv_bias; D.nqkv = nqkv;
     D.rms_eps = m.rms_eps;
     D.tau_dec = c->dc.tau_dec; D.tau_merge = c->dc.tau_merge; D.tau_sync = c->dc.tau_sync;
-    D.refresh_interval = c->dc.refresh_interval; D.leader_rule = c->dc.leader_rule;
+    D.refresh_interval = c->dc.refresh_interval; D.leader_rule = c->dc.leader_rule; D.eos_id = c->dc.eos_id;
     D.max_req = l.max_requests; D.max_br = l.max_branches; D.lpad = lpad; D.n_pages = lpad / BB_PAGE;
     D.gmax = l.max_gen_len; D.rows_cap = rows_cap; D.lm_cap = lm_cap; D.phys_per_req = l.max_branches + 1;
     c->refresh_rows_cap = refresh_rows;
@@ -493,6 +493,7 @@ static int read_stats(bb_ctx* c, int slot, bb_request_stats* out) {
     memset(out, 0, sizeof(*out));
     out->n_branches = H.N; out->refresh_due = H.refresh_due; out->all_done = H.all_done;
     out->nfe_init = H.nfe_init; out->nfe_block = H.nfe_block; out->nfe_refresh = H.nfe_refresh;
+    out->finished = H.finished; out->winner = H.finished ? H.winner : -1; out->eos_pos = H.finished ? H.eos_pos : -1;
     for (int k = 0; k < H.N; ++k) out->branch[k] = br[k];
     return BB_OK;
 }
@@ -503,6 +504,41 @@ extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stat
     if ((rc = upload_req_list(c, ids, n)) != BB_OK) return rc;
     { PROF(BB_K_POLICY, 0, 0); launch_commit_merge(c->D, n, reinterpret_cast<const uint16_t*>(c->lm), c->stream); }
     HIPCHK(c, hipGetLastError());
+    if (stats) {
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        for (int i = 0; i < n; ++i) if ((rc = read_stats(c, ids[i], &stats[i])) != BB_OK) return rc;
+    }
+    return BB_OK;
+}
+
+// ---- Alg. 1 driver --------------------------------------------------------------------------------------
+extern "C" int bb_generate(bb_ctx* c, const int* ids, int n, int max_block_forwards, bb_request_stats* stats) {
+    int rc = check_reqs(c, ids, n, false);
+    if (rc != BB_OK) return rc;
+    if (max_block_forwards < 0) return fail(c, BB_EINVAL, "max_block_forwards must not be negative");
+    for (int i = 0; i < n; ++i)
+        if (c->reqs[ids[i]].initialised) return fail(c, BB_ESTATE, "bb_generate wants requests that have not been initialised");
+    std::vector<int> run(ids, ids + n), next, due;
+    auto poll = [&](const std::vector<int>& list) -> int {       // flags of the listed requests after a commit
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        next.clear(); due.clear();
+        for (int id : list) {
+            ReqHeader h;
+            HIPCHK(c, hipMemcpy(&h, c->D.hdr + id, sizeof(h), hipMemcpyDeviceToHost));
+            if (!h.finished) { next.push_back(id); if (h.refresh_due) due.push_back(id); }
+        }
+        return BB_OK;
+    };
+    for (int id : run) if ((rc = bb_refresh(c, &id, 1, BB_INIT)) != BB_OK) return rc;
+    if ((rc = bb_merge_commit(c, run.data(), n, nullptr)) != BB_OK) return rc;
+    if ((rc = poll(run)) != BB_OK) return rc;
+    for (int fwd = 0; !next.empty() && fwd < max_block_forwards; ++fwd) {
+        run = next;
+        if (!due.empty() && (rc = bb_refresh(c, due.data(), (int)due.size(), BB_PERIODIC)) != BB_OK) return rc;
+        if ((rc = bb_denoise_step(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
+        if ((rc = bb_merge_commit(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
+        if ((rc = poll(run)) != BB_OK) return rc;
+    }
     if (stats) {
         HIPCHK(c, hipStreamSynchronize(c->stream));
         for (int i = 0; i < n; ++i) if ((rc = read_stats(c, ids[i], &stats[i])) != BB_OK) return rc;

@@ -18,6 +18,7 @@ struct ReqHeader {
     int since_refresh, refresh_due, all_done;
     int nfe_init, nfe_block, nfe_refresh;
     int initialised;            // init refresh has run
+    int finished, winner, eos_pos;  // end of Alg. 1: 1 all branches done / 2 EOS winner; output branch; its EOS
     int pending[BB_MAX_BRANCHES];   // branch received logits in the latest forward
 };
 
@@ -31,7 +32,7 @@ struct Dev {
     int nqkv;                   // (hq + 2 hkv) * hd
     float rms_eps;
     // decode
-    float tau_dec, tau_merge; int tau_sync, refresh_interval, leader_rule;
+    float tau_dec, tau_merge; int tau_sync, refresh_interval, leader_rule, eos_id;
     // limits
     int max_req, max_br, lpad, n_pages, gmax, rows_cap, lm_cap;
     int phys_per_req;           // max_br + 1 (last = shared row)

@@ -166,6 +166,7 @@ struct CommitShared {
     int si[4]; float sf[4];
     int decoded[BB_MAX_BRANCHES], order[BB_MAX_BRANCHES], compat[BB_MAX_BRANCHES];
     int n_order, lead, istar, merged, thr, fb, go;
+    int win, win_dec, win_eos;
 };
 
 static __device__ int count_decoded(const Dev& D, const int* Xr, int L_p, int L, int* sh) {
@@ -253,6 +254,37 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
         if (t == 0) {
             B[k].committed_threshold += S.thr; B[k].committed_fallback += S.fb;
             B[k].mean_conf = sc / (float)nm;
+        }
+    }
+    // -- CheckEOS (Alg. 1) on the branches that were just decoded: the branch's EOS is the first generation
+    //    position holding the EOS token, and it is EOS-ready when nothing before that is masked.  A ready
+    //    branch ends the request (most tokens decoded wins, lowest index on ties) before advance / MergeSync.
+    if (D.eos_id >= 0) {
+        __syncthreads();
+        if (t == 0) S.win = -1;
+        for (int k = 0; k < N; ++k) {
+            __syncthreads();
+            if (!H.pending[k] || B[k].done) continue;
+            const int* Xr = X + (size_t)k * D.lpad;
+            int e = 0x7fffffff, fm = 0x7fffffff;
+            for (int i = L_p + t; i < L; i += 256) {
+                if (Xr[i] == D.eos_id) e = min(e, i);
+                if (Xr[i] == mask) fm = min(fm, i);
+            }
+            e = wg_min_i(e, S.si);
+            fm = wg_min_i(fm, S.si);
+            const int c = count_decoded(D, Xr, L_p, L, S.si);
+            if (t == 0 && e != 0x7fffffff && fm > e && (S.win < 0 || c > S.win_dec)) { S.win = k; S.win_dec = c; S.win_eos = e; }
+        }
+        __syncthreads();
+        if (S.win >= 0) {
+            for (int k = 0; k < N; ++k) {
+                const int c = count_decoded(D, X + (size_t)k * D.lpad, L_p, L, S.si);
+                if (t == 0) { B[k].tokens_decoded = c; B[k].done = 1; B[k].start = B[k].end = L; }
+            }
+            if (t < BB_MAX_BRANCHES) H.pending[t] = 0;
+            if (t == 0) { H.finished = 2; H.winner = S.win; H.eos_pos = S.win_eos; H.all_done = 1; H.refresh_due = 0; }
+            return;
         }
     }
     __syncthreads();
@@ -385,6 +417,21 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
         for (int k = 0; k < N; ++k) { B[k].tokens_decoded = S.decoded[k]; all &= B[k].done; }
         H.all_done = all;
         H.refresh_due = H.since_refresh >= D.refresh_interval && !all;
+        S.win = -1;
+        if (all && !H.finished) {       // final selection of Alg. 1: most progress, lowest index on ties
+            int w = 0;
+            for (int k = 1; k < N; ++k) if (S.decoded[k] > S.decoded[w]) w = k;
+            S.win = w;
+        }
+    }
+    __syncthreads();
+    if (S.win >= 0) {
+        const int* Xw = X + (size_t)S.win * D.lpad;
+        int e = 0x7fffffff;
+        if (D.eos_id >= 0)
+            for (int i = L_p + t; i < L; i += 256) if (Xw[i] == D.eos_id) e = min(e, i);
+        e = wg_min_i(e, S.si);
+        if (t == 0) { H.finished = 1; H.winner = S.win; H.eos_pos = e == 0x7fffffff ? -1 : e; }
     }
 }
 

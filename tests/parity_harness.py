@@ -123,7 +123,12 @@ class SideBySide:
                 fragile = True
             if c[-1] < p.tau_dec + GUARD and len(c) > 1 and c[-1] - c[-2] <= GUARD:
                 fragile = True
+        decoded_now = o.decoded_branches()
         commits = o.decode_all()
+        if o.eos_finish(decoded_now):
+            rep.commits += len(commits)
+            self._last = (fragile, commits, [], [])
+            return
         o.advance_all()
         # leader guard band
         td = [tokens_decoded(o.X, k, o.L_p, o.mask_id) for k in range(o.N)]
@@ -152,7 +157,7 @@ class SideBySide:
             return pr
 
         merges, syncs = o.merge_sync_all(prob)
-        o.refresh_due = o.since_refresh >= p.refresh_interval and any(not b.done for b in o.br)
+        o.end_of_commit()
         rep.commits += len(commits); rep.merges += len(merges); rep.syncs += len(syncs)
         self._last = (fragile, commits, merges, syncs)
 
@@ -168,6 +173,7 @@ class SideBySide:
             same &= g.committed_threshold == b.committed_threshold and g.committed_fallback == b.committed_fallback
             same &= g.tokens_decoded == tokens_decoded(o.X, k, o.L_p, o.mask_id)
         same &= bool(st.refresh_due) == bool(o.refresh_due)
+        same &= (st.finished, st.winner, st.eos_pos) == (o.finished, o.winner if o.finished else -1, o.eos_pos if o.finished else -1)
         same &= (st.nfe_init, st.nfe_block, st.nfe_refresh) == (o.nfe["init"], o.nfe["block"], o.nfe["refresh"])
         if fragile:
             rep.fragile_steps += 1

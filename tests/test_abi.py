@@ -54,10 +54,10 @@ def test_workspace_bytes_covers_weights_and_cache(lib, name):
 
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(binding.bb_model_cfg) == 11 * 4
-    assert C.sizeof(binding.bb_decode_cfg) == 5 * 4
+    assert C.sizeof(binding.bb_decode_cfg) == 6 * 4
     assert C.sizeof(binding.bb_limits) == 5 * 4
     assert C.sizeof(binding.BranchState) == 10 * 4
-    assert C.sizeof(binding.RequestStats) == 6 * 4 + 8 * 40
+    assert C.sizeof(binding.RequestStats) == 9 * 4 + 8 * 40
 
 
 def test_bad_shapes_are_rejected(lib):

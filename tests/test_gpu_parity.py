@@ -80,3 +80,108 @@ def test_head_dim_128_small():
     shape = ModelShape("small128", 2, 512, 4, 2, 128, 1024, 2048, lm_std=0.35)
     s = run_case(shape, DecodeParams(0.9, 0.5, 4, 4, 0), 200, 64, (8, 16, 32), seed=8, max_steps=12)
     assert s.rep.max_logit_err <= 3e-2
+
+
+# ---- CheckEOS / winner selection and the Alg. 1 driver ----------------------------------------------------
+def _eos_token_of_plain_run(model, decode, prompt_len, gen_len, blocks, seed, weights):
+    """The token in the middle of the oracle's plain output: used as the EOS id (its first occurrence may be earlier)."""
+    om = OracleModel(model, weights, np.float64)
+    from oracle.blockbatch import OracleRequest
+    rq = OracleRequest(om, gen_prompt(model, seed, 0, prompt_len), gen_len, blocks, decode)
+    row = rq.run()
+    gen = row[prompt_len:]
+    return int(gen[gen_len // 2])
+
+
+@pytest.mark.parametrize("seed,blocks,prompt_len,gen_len", [(0, (8, 16, 32), 64, 64), (11, (4, 8, 16, 32), 50, 96)])
+def test_tiny_eos_parity(seed, blocks, prompt_len, gen_len):
+    import dataclasses
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, seed))
+    eos = _eos_token_of_plain_run(w.model, w.decode, prompt_len, gen_len, blocks, seed, weights)
+    decode = dataclasses.replace(w.decode, eos_id=eos)
+    s = run_case(w.model, decode, prompt_len, gen_len, blocks, seed=seed)
+    assert s.o.finished in (1, 2) and not s.diverged
+    assert s.rep.max_logit_err <= 3e-2
+    print("eos case finished =", s.o.finished, "winner", s.o.winner, "eos_pos", s.o.eos_pos, flush=True)
+
+
+def test_generate_driver_matches_stepwise_calls():
+    """bb_generate (the library's Alg. 1 loop) against the same calls made one by one from Python, with and
+    without an EOS id: identical token rows, winners and NFE counts."""
+    import dataclasses
+    from paper_2605_29233_amd import BB_INIT, BB_PERIODIC
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 0))
+    eos = _eos_token_of_plain_run(w.model, w.decode, 64, 64, w.block_sizes, 0, weights)
+    for decode in (w.decode, dataclasses.replace(w.decode, eos_id=eos)):
+        bb = make_bb(w.model, decode, weights, 3, 128, 64, 2 * sum(w.block_sizes), max_requests=6)
+        try:
+            prompts = [gen_prompt(w.model, 0, r, 64) for r in range(2)]
+            a = [bb.request_open(p, 64, w.block_sizes) for p in prompts]
+            sa = bb.generate(a)
+            b = [bb.request_open(p, 64, w.block_sizes) for p in prompts]
+            for r in b:
+                bb.refresh([r], BB_INIT)
+            st = bb.merge_commit(b)
+            while not all(x.finished for x in st):
+                run = [r for r, x in zip(b, st) if not x.finished]
+                due = [r for r, x in zip(b, st) if not x.finished and x.refresh_due]
+                if due:
+                    bb.refresh(due, BB_PERIODIC)
+                bb.denoise_step(run, want_view=False)
+                new = bb.merge_commit(run)
+                st = [new[run.index(r)] if r in run else x for r, x in zip(b, st)]
+            for ra, rb, xa, xb in zip(a, b, sa, st):
+                assert np.array_equal(bb.get_tokens(ra), bb.get_tokens(rb))
+                assert (xa.finished, xa.winner, xa.eos_pos) == (xb.finished, xb.winner, xb.eos_pos)
+                assert (xa.nfe_init, xa.nfe_block, xa.nfe_refresh) == (xb.nfe_init, xb.nfe_block, xb.nfe_refresh)
+                assert xa.finished in (1, 2) and 0 <= xa.winner < 3
+                if decode.eos_id < 0:
+                    assert xa.finished == 1 and xa.eos_pos == -1
+                if xa.finished == 2:
+                    row = bb.get_tokens(ra)[xa.winner]
+                    assert row[xa.eos_pos] == decode.eos_id and not np.any(row[64:xa.eos_pos] == w.model.mask_id)
+            # a forward limit stops the loop without an error and leaves the request unfinished
+            if decode.eos_id < 0:
+                c = bb.request_open(prompts[0], 64, w.block_sizes)
+                sc = bb.generate([c], max_block_forwards=2)[0]
+                assert sc.finished == 0 and sc.nfe_block == 2 and sc.winner == -1
+        finally:
+            bb.close()
+
+
+def test_tiny_eos_cycle_parity():
+    """An EOS planted behind still-masked positions (same state on both sides): the branches stay in the
+    EOS cycle, decoding on, until some decoded branch has a contiguous prefix; parity holds throughout."""
+    import dataclasses
+    w = workload("tiny")
+    eos = 5
+    decode = dataclasses.replace(w.decode, eos_id=eos)
+    weights = dict(gen_weights(w.model, 3))
+    om = OracleModel(w.model, weights, np.float64)
+    bb = make_bb(w.model, decode, weights, 3, 128, 64, sum(w.block_sizes))
+    try:
+        s = SideBySide(bb, om, gen_prompt(w.model, 3, 0, 64), 64, w.block_sizes, decode)
+        s.init()
+        s.commit()
+        planted = 0
+        for br in s.o.br:
+            masked = [i for i in range(br.start, br.end) if s.o.X[br.k, i] == s.o.mask_id]
+            if not br.done and len(masked) >= 3:
+                s.o.X[br.k, masked[-1]] = eos
+                planted += 1
+        assert planted > 0 and not np.any(s.o.X[:, :64] == eos)
+        bb.set_state(s.rid, s.o.X, s.o.br)
+        n = 0
+        while not s.o.finished and n < 60:
+            if s.o.refresh_due:
+                s.refresh()
+            s.step()
+            s.commit()
+            n += 1
+        print("eos cycle: finished", s.o.finished, "after", n, "steps; winner", s.o.winner, "eos_pos", s.o.eos_pos, s.rep, flush=True)
+        assert s.o.finished == 2 and n >= 2 and not s.diverged
+        assert s.rep.max_logit_err <= 3e-2
+    finally:
+        bb.close()
