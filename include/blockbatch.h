@@ -173,6 +173,19 @@ int bb_merge_commit(bb_ctx* ctx, const int* req_ids_host, int n, bb_request_stat
  * Returns BB_OK also when the forward limit stopped it (finished == 0 then). */
 int bb_generate(bb_ctx* ctx, const int* req_ids_host, int n, int max_block_forwards, bb_request_stats* stats_out_host);
 
+/* KV-consistency diagnostics of App. A.2 on the flattened cache state (all layers, keys and values) of
+ * the branches of one initialised request:
+ *   D_pair_host [N][N]: squared distance between the cache rows of branches i and j; *D_avg_host: their
+ *                       mean over ordered pairs i != j (branch dispersion D_t);
+ *   E_host [N]:         cache-consistency error ||K - F(x)||_2 of each unfinished branch (0 for finished ones).
+ * E needs F(x): the call snapshots the rows into scratch_dev, runs bb_refresh(BB_PERIODIC) on the request
+ * (so it counts as a refresh: K <- F(x) afterwards, refresh counters reset) and compares.  Pass E_host =
+ * NULL to get the dispersion only, without scratch and without a refresh.  scratch_dev: device memory of
+ * at least bb_kv_diag_scratch_bytes(), 16-byte aligned.  Synchronises the stream. */
+size_t bb_kv_diag_scratch_bytes(bb_ctx* ctx, int req_id);
+int bb_kv_diagnostics(bb_ctx* ctx, int req_id, void* scratch_dev, size_t scratch_bytes, double* E_host,
+                      double* D_pair_host, double* D_avg_host);
+
 /* ---- inspection and teacher forcing (tests, harness); all synchronise the stream ---- */
 /* Device pointers to the results of the latest forward (what bb_denoise_step returns in
  * view_out; after bb_refresh(BB_INIT) of one request the rows are its G generation positions). */

@@ -64,7 +64,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -104,6 +104,9 @@ def load_library():
         lib.bb_profile_enable.argtypes = [C.c_void_p, C.c_int]
         lib.bb_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]
         lib.bb_debug_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
+        lib.bb_kv_diag_scratch_bytes.restype = C.c_size_t
+        lib.bb_kv_diag_scratch_bytes.argtypes = [C.c_void_p, C.c_int]
+        lib.bb_kv_diagnostics.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.bb_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         lib.bb_debug_copy16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         _LIB = lib
@@ -250,6 +253,22 @@ class BlockBatch:
         st = (RequestStats * n)()
         self._chk(self.lib.bb_generate(self._ctx, p, n, int(max_block_forwards), C.cast(st, C.c_void_p)), "bb_generate")
         return list(st)
+
+    def kv_diagnostics(self, rid, want_error=True):
+        """(E [N] or None, pairwise squared distances [N][N], D_t) of App. A.2; want_error runs a refresh."""
+        import torch
+        n, _ = self._req[rid]
+        Dp = np.zeros((n, n), dtype=np.float64)
+        Da = C.c_double(0.0)
+        E, scratch, nbytes = None, None, 0
+        if want_error:
+            E = np.zeros(n, dtype=np.float64)
+            nbytes = self.lib.bb_kv_diag_scratch_bytes(self._ctx, rid)
+            scratch = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._chk(self.lib.bb_kv_diagnostics(self._ctx, rid, C.c_void_p(scratch.data_ptr()) if want_error else None, nbytes,
+                                             E.ctypes.data_as(C.c_void_p) if want_error else None,
+                                             Dp.ctypes.data_as(C.c_void_p), C.byref(Da)), "bb_kv_diagnostics")
+        return E, Dp, Da.value
 
     # -- inspection ---------------------------------------------------------------------------
     def synchronize(self):

@@ -681,6 +681,78 @@ extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float
     return BB_OK;
 }
 
+// ---- KV-consistency diagnostics -----------------------------------------------------------------------
+extern "C" size_t bb_kv_diag_scratch_bytes(bb_ctx* c, int id) {
+    if (check_one(c, id) != BB_OK) return 0;
+    const HostReq& R = c->reqs[id];
+    const size_t pages = (R.L + BB_PAGE - 1) / BB_PAGE;
+    const size_t row = (size_t)c->m.n_layers * pages * c->m.n_kv_heads * BB_PAGE * 2 * c->m.head_dim * sizeof(half_t);
+    return 2 * row * R.N + align_up((size_t)c->m.n_layers * pages * sizeof(double), 256);     // K and V snapshots + partial sums
+}
+
+extern "C" int bb_kv_diagnostics(bb_ctx* c, int id, void* scratch, size_t scratch_bytes, double* E, double* Dpair, double* Davg) {
+    if (check_one(c, id) != BB_OK) return BB_EINVAL;
+    const HostReq& R = c->reqs[id];
+    if (!R.initialised) return fail(c, BB_ESTATE, "request has not had its initial refresh");
+    const int pages = (R.L + BB_PAGE - 1) / BB_PAGE, n_part = c->m.n_layers * pages;
+    const size_t part_bytes = align_up((size_t)n_part * sizeof(double), 256);
+    if (E && (!scratch || (uintptr_t)scratch % 16 || scratch_bytes < bb_kv_diag_scratch_bytes(c, id)))
+        return fail(c, BB_EINVAL, "bb_kv_diagnostics: scratch missing, misaligned or too small");
+    std::vector<double> host(n_part);
+    double* part = E ? reinterpret_cast<double*>(scratch) : reinterpret_cast<double*>(c->dbg);    // dbg holds 2 L hkv hd floats >= n_part doubles
+    auto total = [&](double* dst) -> int {
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        HIPCHK(c, hipMemcpy(host.data(), part, n_part * sizeof(double), hipMemcpyDeviceToHost));
+        double t = 0.0;
+        for (double v : host) t += v;
+        *dst = t;
+        return BB_OK;
+    };
+    int rc;
+    const int g0 = id * c->D.max_br;
+    if (Dpair || Davg) {
+        double sum = 0.0;
+        for (int i = 0; i < R.N; ++i)
+            for (int j = i; j < R.N; ++j) {
+                double v = 0.0;
+                if (j > i) {
+                    launch_kv_sqdist(c->D, g0 + i, g0 + j, nullptr, nullptr, 0, 0, pages, part, c->stream);
+                    if ((rc = total(&v)) != BB_OK) return rc;
+                    sum += 2 * v;
+                }
+                if (Dpair) Dpair[i * R.N + j] = Dpair[j * R.N + i] = v;
+            }
+        if (Davg) *Davg = R.N > 1 ? sum / ((double)R.N * (R.N - 1)) : 0.0;
+    }
+    if (E) {
+        bb_branch_state br[BB_MAX_BRANCHES];
+        HIPCHK(c, hipStreamSynchronize(c->stream));
+        HIPCHK(c, hipMemcpy(br, c->D.br + g0, sizeof(bb_branch_state) * c->D.max_br, hipMemcpyDeviceToHost));
+        half_t* snapK = reinterpret_cast<half_t*>(reinterpret_cast<char*>(scratch) + part_bytes);
+        const size_t row_halfs = (size_t)c->m.n_layers * pages * c->m.n_kv_heads * BB_PAGE * 2 * c->m.head_dim;
+        half_t* snapV = snapK + row_halfs * R.N;
+        bool any = false;
+        for (int k = 0; k < R.N; ++k) {
+            E[k] = 0.0;
+            if (br[k].done) continue;
+            any = true;
+            launch_kv_snapshot(c->D, g0 + k, snapK, snapV, R.N, k, pages, c->stream);
+        }
+        if (any) {
+            if ((rc = bb_refresh(c, &id, 1, BB_PERIODIC)) != BB_OK) return rc;
+            for (int k = 0; k < R.N; ++k) {
+                if (br[k].done) continue;
+                launch_kv_sqdist(c->D, g0 + k, 0, snapK, snapV, R.N, k, pages, part, c->stream);
+                double v = 0.0;
+                if ((rc = total(&v)) != BB_OK) return rc;
+                E[k] = std::sqrt(v);
+            }
+        }
+    }
+    HIPCHK(c, hipGetLastError());
+    return BB_OK;
+}
+
 // ---- traffic-counter reference ----------------------------------------------------------------------
 __global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];

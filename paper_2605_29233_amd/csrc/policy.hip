@@ -457,3 +457,68 @@ __global__ void read_kv_kernel(Dev D, int gbr, int layer, float* __restrict__ K,
 void launch_read_kv(const Dev& D, int slot, int branch, int layer, float* K, float* V, int L, hipStream_t s) {
     read_kv_kernel<<<1024, 256, 0, s>>>(D, slot * D.max_br + branch, layer, K, V, L);
 }
+
+// ---- KV-consistency diagnostics (App. A.2) ---------------------------------------------------------
+// Squared distance between two cache rows, per (layer, page): out[(layer * n_pages + page)] = sum over the
+// page's K and V blocks of ((a_hi + a_lo) - (b_hi + b_lo))^2 in fp64.  A row is either a branch's view of
+// the cache (page table -> physical row) or row `b_row` of a snapshot buffer with the cache's block layout
+// ([layer][row][page][kv head]).  Both sides use the same fragment order, so elements pair up by offset.
+__global__ __launch_bounds__(256) void kv_sqdist_kernel(Dev D, int gbr_a, int gbr_b, const half_t* __restrict__ snapK,
+                                                        const half_t* __restrict__ snapV, int snap_rows, int b_row,
+                                                        int n_pages_used, double* __restrict__ out) {
+    __shared__ double sh[4];
+    const int layer = blockIdx.y, page = blockIdx.x;
+    const int pa = D.table[(size_t)gbr_a * D.n_pages + page];
+    const size_t blk = (size_t)D.hkv * BB_PAGE * 2 * D.hd;              // halfs per page of one row
+    const half_t *ka = D.Kc + kv_block_off(D, layer, pa, page, 0), *va = D.Vt + kv_block_off(D, layer, pa, page, 0);
+    const half_t *kb, *vb;
+    bool same = false;
+    if (snapK) {
+        const size_t off = (((size_t)layer * snap_rows + b_row) * n_pages_used + page) * blk;
+        kb = snapK + off; vb = snapV + off;
+    } else {
+        const int pb = D.table[(size_t)gbr_b * D.n_pages + page];
+        same = pb == pa;
+        kb = D.Kc + kv_block_off(D, layer, pb, page, 0); vb = D.Vt + kv_block_off(D, layer, pb, page, 0);
+    }
+    double acc = 0.0;
+    if (!same) {
+        // fragment pair f: hi term at 16-byte piece (2 f) * 64 + lane, lo term 64 pieces further
+        const int n_frag = (int)(blk / 8 / 128);
+        for (int it = threadIdx.x; it < n_frag * 64; it += 256) {
+            const size_t q = (size_t)(it / 64) * 128 + it % 64;
+            for (int op = 0; op < 2; ++op) {
+                const half_t* a = (op ? va : ka) + q * 8; const half_t* b = (op ? vb : kb) + q * 8;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const double x = ((double)(float)a[j] + (double)(float)a[j + 512]) - ((double)(float)b[j] + (double)(float)b[j + 512]);
+                    acc += x * x;
+                }
+            }
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) out[(size_t)layer * n_pages_used + page] = sh[0] + sh[1] + sh[2] + sh[3];
+}
+
+// Copy a branch's view of the cache into row `row` of a snapshot buffer.
+__global__ __launch_bounds__(256) void kv_snapshot_kernel(Dev D, int gbr, half_t* __restrict__ snapK, half_t* __restrict__ snapV,
+                                                          int snap_rows, int row, int n_pages_used) {
+    const int layer = blockIdx.y, page = blockIdx.x;
+    const int phys = D.table[(size_t)gbr * D.n_pages + page];
+    const size_t blk = (size_t)D.hkv * BB_PAGE * 2 * D.hd, off = (((size_t)layer * snap_rows + row) * n_pages_used + page) * blk;
+    const u32x4* ks = reinterpret_cast<const u32x4*>(D.Kc + kv_block_off(D, layer, phys, page, 0));
+    const u32x4* vs = reinterpret_cast<const u32x4*>(D.Vt + kv_block_off(D, layer, phys, page, 0));
+    u32x4* kd = reinterpret_cast<u32x4*>(snapK + off); u32x4* vd = reinterpret_cast<u32x4*>(snapV + off);
+    for (int i = threadIdx.x; i < (int)(blk / 8); i += 256) { kd[i] = ks[i]; vd[i] = vs[i]; }
+}
+
+void launch_kv_sqdist(const Dev& D, int gbr_a, int gbr_b, const half_t* snapK, const half_t* snapV, int snap_rows, int b_row,
+                      int n_pages_used, double* out, hipStream_t s) {
+    kv_sqdist_kernel<<<dim3(n_pages_used, D.n_layers), 256, 0, s>>>(D, gbr_a, gbr_b, snapK, snapV, snap_rows, b_row, n_pages_used, out);
+}
+void launch_kv_snapshot(const Dev& D, int gbr, half_t* snapK, half_t* snapV, int snap_rows, int row, int n_pages_used, hipStream_t s) {
+    kv_snapshot_kernel<<<dim3(n_pages_used, D.n_layers), 256, 0, s>>>(D, gbr, snapK, snapV, snap_rows, row, n_pages_used);
+}

@@ -185,3 +185,49 @@ def test_tiny_eos_cycle_parity():
         assert s.rep.max_logit_err <= 3e-2
     finally:
         bb.close()
+
+
+def test_kv_diagnostics_match_oracle():
+    """Cache-consistency error E_t and branch dispersion D_t (App. A.2) from the cache pages against the oracle's
+    fp64 definitions, mid-trajectory; the error query doubles as a refresh on both sides."""
+    from oracle.diagnostics import cache_error, dispersion
+    w = workload("tiny")
+    decode = DecodeParams(0.97, 0.5, 64, 100, 0)              # slow commits, no sync, no periodic refresh
+    weights = dict(gen_weights(w.model, 5))
+    om = OracleModel(w.model, weights, np.float64)
+    bb = make_bb(w.model, decode, weights, 3, 200, 128, sum(w.block_sizes))
+    try:
+        s = SideBySide(bb, om, gen_prompt(w.model, 5, 0, 72), 128, w.block_sizes, decode)
+        s.init()
+        E, P, D = bb.kv_diagnostics(s.rid, want_error=False)
+        assert E is None and D == 0.0 and not P.any()          # every branch still points at the shared row
+        s.commit()
+        for _ in range(3):
+            s.step()
+            s.commit()
+        assert not s.o.all_done() and not s.diverged
+        Pref, Dref = dispersion(s.o)
+        _, P, D = bb.kv_diagnostics(s.rid, want_error=False)
+        scale = max(Pref.max(), 1e-30)
+        print("dispersion: oracle", Dref, "gpu", D, flush=True)
+        assert Dref > 0 and np.abs(P - Pref).max() <= 2e-3 * scale and abs(D - Dref) <= 2e-3 * Dref
+        active = [b.k for b in s.o.br if not b.done]
+        Eref = cache_error(s.o)
+        E, _, _ = bb.kv_diagnostics(s.rid)
+        s.o.refresh()                                          # the query refreshed the GPU side
+        print("cache error: oracle", Eref, "gpu", E.tolist(), flush=True)
+        for k in range(s.o.N):
+            if k in active:
+                assert Eref[k] > 0 and abs(E[k] - Eref[k]) <= 2e-3 * Eref[k]
+            else:
+                assert E[k] == 0.0
+        st = bb.get_stats(s.rid)
+        assert st.nfe_refresh == s.o.nfe["refresh"] == 1
+        E2, _, _ = bb.kv_diagnostics(s.rid)                    # K = F(x) now: the error of a refreshed row is zero
+        s.o.refresh()
+        assert np.all(E2 <= 1e-6 * max(Eref))
+        s.step()                                               # and the trajectory continues in parity
+        s.commit()
+        assert s.rep.max_logit_err <= 3e-2
+    finally:
+        bb.close()
