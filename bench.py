@@ -3,7 +3,8 @@
 A "step" is one pass of the whole hot path: bb_denoise_step (pack, batched block forward, LM
 head, vocabulary reduction) + bb_merge_commit (Eq. 1 commit, merge, sync), plus the periodic
 full-sequence refresh whenever R block forwards have run.  `value` is steps/s of a free-running
-decode (refreshes included, inputs and weights resident in HBM); the steady-state block forward,
+decode (refreshes included, inputs and weights resident in HBM; a request that finishes inside the
+timed region is opened again, so every counted step is a real block forward); the steady-state block forward,
 the refresh and the committed-token rate are reported beside it.  The roofline figure is for the
 weight-streaming MFMA GEMM launches of the block forward at a frozen, fully masked state, timed
 with HIP events on the library's stream; the CPU oracle is timed on the host for reference.
@@ -35,6 +36,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--workload", default="llada")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--refresh-interval", type=int, default=0, help="override the workload's R (App. E.3 sweeps)")
+    ap.add_argument("--tau-sync", type=int, default=-1, help="override the workload's tau_sync (App. E.3 sweeps)")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -49,6 +52,12 @@ def main():
     from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT, BB_PERIODIC
 
     w = workload(args.workload)
+    if args.refresh_interval > 0 or args.tau_sync >= 0:
+        import dataclasses
+        d = w.decode
+        d = dataclasses.replace(d, refresh_interval=args.refresh_interval if args.refresh_interval > 0 else d.refresh_interval,
+                                tau_sync=args.tau_sync if args.tau_sync >= 0 else d.tau_sync)
+        w = dataclasses.replace(w, decode=d)
     m = w.model
     L = max(w.prompt_lens) + w.gen_len
     step_rows = w.n_requests * sum(min(b, w.gen_len) for b in w.block_sizes)
@@ -101,20 +110,49 @@ def main():
     refresh_ms = (time.perf_counter() - t0) * 1e3
 
     # ---- 4. free-running decode: the timed region ---------------------------------------------------
-    since = 0
+    # Every timed step is a real block forward: the per-request flags are read back after each commit (one
+    # small copy; the launches of the next step still run ahead of the GPU), a refresh runs when a request
+    # says it is due, and a request that has finished is closed and opened again (its initial full forward
+    # and first commit then fall inside the timed region as extra work, not as a step).
+    tally = {"committed": 0, "refresh": 0, "init": 0, "completed": 0}
+    prev = {}
+
+    def account(r, st):
+        d = sum(st.branch[k].tokens_decoded for k in range(st.n_branches))
+        a = prev.get(r, (0, 0))
+        tally["committed"] += d - a[0]
+        tally["refresh"] += st.nfe_refresh - a[1]
+        prev[r] = (d, st.nfe_refresh)
+
+    def restart(i):
+        bb.request_close(ids[i])
+        ids[i] = bb.request_open(gen_prompt(m, w.seed, i, w.prompt_lens[i]), w.gen_len, w.block_sizes)
+        bb.refresh([ids[i]], BB_INIT)
+        st = bb.merge_commit([ids[i]])[0]
+        prev.pop(ids[i], None)
+        tally["init"] += 1
+        return st
+
+    stats = [restart(i) for i in range(len(ids))]
 
     def one_step():
-        nonlocal since
+        due = [r for r, st in zip(ids, stats) if st.refresh_due and not st.finished]
+        if due:
+            bb.refresh(due, BB_PERIODIC)
         bb.denoise_step(ids, want_view=False)
-        bb.merge_commit(ids, want_stats=False)
-        since += 1
-        if since >= R:
-            bb.refresh(ids, BB_PERIODIC)
-            since = 0
+        new = bb.merge_commit(ids)
+        for i, st in enumerate(new):
+            account(ids[i], st)
+            if st.finished:
+                tally["completed"] += 1
+                st = restart(i)
+                account(ids[i], st)
+            stats[i] = st
 
     for _ in range(args.warmup):
         one_step()
-    s0 = [bb.get_stats(r) for r in ids]
+    for k in tally:
+        tally[k] = 0
     bb.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -123,10 +161,8 @@ def main():
     bb.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    s1 = [bb.get_stats(r) for r in ids]
-    finished_early = any(st.all_done for st in s1)
-    n_refresh = sum(b.nfe_refresh - a.nfe_refresh for a, b in zip(s0, s1)) // max(len(ids), 1)
-    committed = decoded(s1) - decoded(s0)
+    n_refresh = tally["refresh"] // max(len(ids), 1)
+    committed = tally["committed"]
     ms_per_step = dt * 1e3 / args.steps
 
     out = {
@@ -136,9 +172,9 @@ def main():
         "dtype": "bf16 weights x (bf16 hi+lo) activations, fp32 accumulate", "data": "synthetic",
         "config": {"workload": w.name, "model_shape": m.name, "requests": w.n_requests, "prompt_len": list(w.prompt_lens),
                    "gen_len": w.gen_len, "block_sizes": list(w.block_sizes), "packed_rows": step_rows,
-                   "refresh_interval": R, "tau_dec": w.decode.tau_dec},
+                   "refresh_interval": R, "tau_dec": w.decode.tau_dec, "tau_sync": w.decode.tau_sync},
         "committed_tokens_per_s": committed / dt, "committed_tokens": committed, "refreshes_in_timed_region": int(n_refresh),
-        "finished_early": bool(finished_early),
+        "requests_completed_in_timed_region": tally["completed"], "initial_forwards_in_timed_region": tally["init"],
         "block_forward_ms_steady": fwd_ms, "block_forward_steps_per_s_steady": 1e3 / fwd_ms, "refresh_ms": refresh_ms,
         "kernel_ms_per_block_forward": per_step,
         "roofline": {"bound": "hbm", "kernel": "gemm_kernel (weight-streaming MFMA GEMM, block forward)",
