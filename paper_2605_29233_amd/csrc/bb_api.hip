@@ -37,24 +37,33 @@ struct bb_ctx {
     int last_forward_rows, last_lm_cap;
     // per-launch event timing (bb_profile_*)
     int prof_on;
-    struct ProfRec { hipEvent_t a, b; int klass; double bytes, flops; };
+    struct ProfRec { hipEvent_t a, b; int klass; double bytes, flops; bool own_a; };
     std::vector<ProfRec> prof;
     std::vector<hipEvent_t> ev_pool;
+    bool prof_chain;                    // inside a forward: launches are back to back, one event per boundary
+    hipEvent_t prof_prev_end;
 };
 
-// Bracket one launch with events when profiling is on.
+// Bracket one launch with events when profiling is on.  Inside a forward the launches follow each other
+// without anything in between, so the end event of one launch also serves as the start of the next:
+// one event packet per kernel boundary keeps the timeline close to the unprofiled one.
 struct ProfScope {
     bb_ctx* c; int idx;
     ProfScope(bb_ctx* c_, int klass, double bytes, double flops) : c(c_), idx(-1) {
         if (!c->prof_on) return;
         auto get = [&]() { hipEvent_t e; if (c->ev_pool.empty()) { if (hipEventCreate(&e) != hipSuccess) return (hipEvent_t) nullptr; }
                            else { e = c->ev_pool.back(); c->ev_pool.pop_back(); } return e; };
-        bb_ctx::ProfRec r{get(), get(), klass, bytes, flops};
+        const bool chain = c->prof_chain && c->prof_prev_end;
+        bb_ctx::ProfRec r{chain ? c->prof_prev_end : get(), get(), klass, bytes, flops, !chain};
         if (!r.a || !r.b) return;
-        (void)hipEventRecord(r.a, c->stream);
+        if (!chain) (void)hipEventRecord(r.a, c->stream);
         c->prof.push_back(r); idx = (int)c->prof.size() - 1;
     }
-    ~ProfScope() { if (idx >= 0) (void)hipEventRecord(c->prof[idx].b, c->stream); }
+    ~ProfScope() {
+        if (idx < 0) return;
+        (void)hipEventRecord(c->prof[idx].b, c->stream);
+        c->prof_prev_end = c->prof[idx].b;
+    }
 };
 #define PROF(klass, bytes, flops) ProfScope prof_scope_(c, klass, bytes, flops)
 
@@ -409,7 +418,9 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         launch_gemm(W, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr);
         return fused ? 0 : p.split_k;
     };
+    c->prof_chain = false;              // the first launch records its own start
     { PROF(BB_K_GLUE, 0, 0); launch_embed(D, c->emb, c->h, rows_cap, s); }
+    c->prof_chain = true;
     int s_down = 0;
     const size_t pstride = (size_t)rows_pad * d;
     for (int li = 0; li < m.n_layers; ++li) {
@@ -434,6 +445,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         gemm(0, c->lm, c->Apk, c->logits, m.vocab, d, lm_cap, mt_lm, lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE);
         { PROF(BB_K_GLUE, 0, 0); launch_vocab_reduce(D, c->logits, lm_cap, mode == 1, s); }
     }
+    c->prof_chain = false;
     c->last_forward_rows = rows_cap; c->last_lm_cap = lm_cap;
     HIPCHK(c, hipGetLastError());
     return BB_OK;
@@ -574,9 +586,11 @@ extern "C" int bb_profile_read(bb_ctx* c, bb_profile_entry* out, int max_entries
         if (hipEventElapsedTime(&ms, r.a, r.b) == hipSuccess) {
             acc[r.klass].launches += 1; acc[r.klass].total_ms += ms; acc[r.klass].bytes += r.bytes; acc[r.klass].flops += r.flops;
         }
-        c->ev_pool.push_back(r.a); c->ev_pool.push_back(r.b);
+        if (r.own_a) c->ev_pool.push_back(r.a);
+        c->ev_pool.push_back(r.b);
     }
     c->prof.clear();
+    c->prof_prev_end = nullptr;
     int n = 0;
     for (int k = 0; k < BB_K_CLASSES && n < max_entries; ++k) out[n++] = acc[k];
     *n_out = n;
