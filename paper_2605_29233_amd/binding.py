@@ -144,7 +144,7 @@ class StepView:
 
 
 class BlockBatch:
-    def __init__(self, model, decode, limits: Limits, device="cuda:0", stream=None):
+    def __init__(self, model, decode, limits: Limits, device="cuda:0", stream=None, poison_workspace=False):
         import torch
         self.lib = load_library()
         self.model, self.decode, self.limits = model, decode, limits
@@ -160,6 +160,8 @@ class BlockBatch:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        if poison_workspace:        # tests: the library must not rely on what the caller's memory held (0xFF.. = NaN patterns)
+            self._ws.fill_(0xFF)
         base = (self._ws.data_ptr() + 255) // 256 * 256
         self._stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         self._ctx = C.c_void_p()

@@ -219,7 +219,7 @@ class SideBySide:
             assert err <= tol_rel * scale + 1e-6, f"cache differs: {err} vs scale {scale}"
 
 
-def make_bb(model, decode, weights, n_branches, L, G, step_rows, max_requests=1, device="cuda:0"):
-    bb = BlockBatch(model, decode, Limits(max_requests, n_branches, L, G, step_rows), device=device)
+def make_bb(model, decode, weights, n_branches, L, G, step_rows, max_requests=1, device="cuda:0", poison=False):
+    bb = BlockBatch(model, decode, Limits(max_requests, n_branches, L, G, step_rows), device=device, poison_workspace=poison)
     bb.load_weights(weights.items() if hasattr(weights, "items") else weights)
     return bb

@@ -231,3 +231,57 @@ def test_kv_diagnostics_match_oracle():
         assert s.rep.max_logit_err <= 3e-2
     finally:
         bb.close()
+
+
+def test_poisoned_workspace_and_determinism():
+    """The library initialises what it reads: a context on memory filled with 0xFF bytes (NaN patterns in every
+    float format, unaligned d_ffn so padded k columns exist) decodes exactly like one on fresh memory, and two
+    runs of the same request give the same bits."""
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 2))
+    prompt = gen_prompt(w.model, 2, 0, 70)
+    outs = []
+    for poison in (False, True, True):
+        bb = make_bb(w.model, w.decode, weights, 3, 70 + 60, 60, sum(w.block_sizes), max_requests=2, poison=poison)
+        try:
+            r = bb.request_open(prompt, 60, w.block_sizes)
+            bb.refresh([r], 0)
+            logits0 = bb.latest_view().logits().copy()
+            st = bb.generate([bb.request_open(prompt, 60, w.block_sizes)])[0]
+            outs.append((logits0, bb.get_tokens(1).copy(), (st.finished, st.winner, st.nfe_block, st.nfe_refresh)))
+        finally:
+            bb.close()
+    for lg, X, st in outs[1:]:
+        assert np.isfinite(lg[:, :-1]).all()
+        assert np.array_equal(lg[:, :-1], outs[0][0][:, :-1])
+        assert np.array_equal(X, outs[0][1]) and st == outs[0][2]
+
+
+def test_error_paths():
+    from paper_2605_29233_amd import BBError
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 0))
+    bb = make_bb(w.model, w.decode, weights, 3, 128, 64, sum(w.block_sizes), max_requests=2)
+    try:
+        p = gen_prompt(w.model, 0, 0, 64)
+        r = bb.request_open(p, 64, w.block_sizes)
+        with pytest.raises(BBError):
+            bb.denoise_step([r])                     # no initial forward yet
+        with pytest.raises(BBError):
+            bb.request_open(p, 200, w.block_sizes)   # longer than the limits
+        with pytest.raises(BBError):
+            bb.request_open(p, 64, (8, 16, 32, 64))  # more branches than the limits
+        bb.refresh([r], 0)
+        with pytest.raises(BBError):
+            bb.refresh([r], 0)                       # second initial forward
+        with pytest.raises(BBError):
+            bb.denoise_step([r, r])                  # listed twice
+        with pytest.raises(BBError):
+            bb.denoise_step([1])                     # not open
+        with pytest.raises(BBError):
+            bb.generate([r])                         # already initialised
+        bb.merge_commit([r])
+        bb.denoise_step([r])                         # and the context still works after the rejected calls
+        assert bb.merge_commit([r])[0].nfe_block == 1
+    finally:
+        bb.close()
