@@ -83,10 +83,10 @@ struct Bump {
 };
 
 // Largest split-K output over every row count the forward may be called with.
-static size_t buf_elems(int rows_cap, int N, int K) {
+static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
     size_t best = 0;
     for (int rows = 32; rows <= (rows_cap + 31) / 32 * 32; rows += 32) {
-        GemmPlan p = gemm_plan(rows, N, K, 0, 0);
+        GemmPlan p = gemm_plan(rows, N, K, 0, rows > 128 ? forced_nt_wide : 0);
         size_t e = (size_t)p.split_k * rows * N;
         if (e > best) best = e;
     }
@@ -166,7 +166,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     c->Q = b.take<half_t>((size_t)rows_pad * nq * 2);
     c->qkv_elems = buf_elems(rows_cap, nqkv, m.d_model);
     c->part_elems = std::max(buf_elems(rows_cap, m.d_model, nq), buf_elems(rows_cap, m.d_model, m.d_ffn));
-    c->gu_elems = buf_elems(rows_cap, c->ngu, m.d_model);
+    c->gu_elems = buf_elems(rows_cap, c->ngu, m.d_model, 2);
     c->qkv = b.take<float>(c->qkv_elems);
     c->part = b.take<float>(c->part_elems);
     c->gu = b.take<float>(c->gu_elems);
@@ -411,7 +411,9 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     // is not split (then 0 is returned and no partial sums exist)
     auto gemm = [&](int kind, const u32x4* W, const u32x4* A, float* P, int N, int K, int rows, int mtt, int klass,
                     u32x4* swiglu_out = nullptr) {
-        GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, c->force_nt[kind]);
+        // with many rows the gate/up projection keeps 256-column tiles: its fused SwiGLU epilogue pairs two tiles per wave
+        const int nt = c->force_nt[kind] > 0 ? c->force_nt[kind] : (swiglu_out && rows > 128 ? 2 : 0);
+        GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, nt);
         if (c->force_split[kind] > 0 && kind != 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
         const bool fused = swiglu_out && p.split_k == 1 && p.nt == 2;
         PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);

@@ -244,35 +244,37 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     }
     // C^T accumulator layout of the 32x32 MFMA: register r of lane l holds
     //   weight row n = 8*(r/4) + 4*(l/32) + r%4 of the tile, activation row m = l%32.
-    // The tile goes through LDS (each wave its own slice, two m-tiles at a time) so that the global
+    // The tile goes through LDS (each wave its own slice, one or two m-tiles at a time) so that the global
     // stores are whole 128-byte lines of a row instead of 16-byte pieces of 32 different rows.
     constexpr int COLS = 32 * NT, LDT = COLS + 4;          // row stride in floats (16-byte aligned, conflict-free)
+    constexpr int MPP = NT <= 2 ? 2 : 1;                   // m-tiles per pass: four slices of 32 MPP rows must fit the 96 KiB
+    static_assert(4 * 32 * MPP * LDT * 4 <= (int)sizeof(lds), "store slices exceed the staging buffers");
     __syncthreads();                                        // all waves are done with the staged activations
-    float* tl = reinterpret_cast<float*>(&lds[0][0]) + wave * (64 * LDT);
+    float* tl = reinterpret_cast<float*>(&lds[0][0]) + wave * (32 * MPP * LDT);
     float* Ps = P + (size_t)split_id * split_stride;
     const int x0 = (bx * 4 + wave) * NT;                    // first weight tile of this wave
 #pragma unroll
-    for (int half = 0; half < 2; ++half) {
+    for (int pass = 0; pass < MT / MPP; ++pass) {
 #pragma unroll
         for (int t = 0; t < NT; ++t)
 #pragma unroll
-            for (int mh = 0; mh < 2; ++mh)
+            for (int mh = 0; mh < MPP; ++mh)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const f32x16& a4 = acc[t][2 * half + mh];
+                    const f32x16& a4 = acc[t][MPP * pass + mh];
                     *reinterpret_cast<float4*>(&tl[(mh * 32 + (lane & 31)) * LDT + t * 32 + 8 * q + 4 * (lane >> 5)]) =
                         make_float4(a4[4 * q], a4[4 * q + 1], a4[4 * q + 2], a4[4 * q + 3]);
                 }
         // (same wave wrote and reads: no barrier needed, the LDS counter orders them)
         constexpr int LPR = COLS / 4;                       // lanes per row
-        const int rows_valid = min(64, (mt_cnt - 2 * half) * 32);
+        const int rows_valid = min(32 * MPP, (mt_cnt - MPP * pass) * 32);
 #pragma unroll
-        for (int it = 0; it < 64 * LPR / 64; ++it) {
-            const int r = it * (64 / LPR) + lane / LPR, c4 = (lane % LPR) * 4;
+        for (int it = 0; it < 32 * MPP * LPR / 64; ++it) {
+            const int idx = it * 64 + lane, r = idx / LPR, c4 = (idx % LPR) * 4;
             const float4 v = *reinterpret_cast<const float4*>(&tl[r * LDT + c4]);
             const int n = x0 * 32 + c4;
             if (r < rows_valid && n < n_tiles * 32)
-                *reinterpret_cast<float4*>(&Ps[(size_t)((mt0 + 2 * half) * 32 + r) * ldp + n]) = v;
+                *reinterpret_cast<float4*>(&Ps[(size_t)((mt0 + MPP * pass) * 32 + r) * ldp + n]) = v;
         }
     }
     __syncthreads();                                        // the next tile's prologue overwrites the LDS slices
@@ -286,7 +288,12 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
     GemmPlan p;
     p.nt = forced_nt > 0 ? forced_nt : (n_tiles >= 8 ? 2 : 1);
     if (forced_nt <= 0 && m_groups == 1 && N <= 8192) p.nt = 1;     // few columns: narrower tiles, fewer splits
-    if (p.nt == 2 && n_tiles < 8) p.nt = 1;
+    if (p.nt >= 2 && n_tiles < 4 * p.nt) p.nt = 1;
+    if (forced_nt <= 0 && m_groups > 1 && p.nt == 2 && n_tiles >= 12) {
+        // many rows: 384-column tiles when they need fewer rounds of workgroups (a tile costs in proportion to its width)
+        auto rounds = [&](int nt) { return (long)(((n_tiles + 4 * nt - 1) / (4 * nt)) * (long)m_groups + 255) / 256 * nt; };
+        if (rounds(3) < rounds(2)) p.nt = 3;
+    }
     const int n_groups = (n_tiles + 4 * p.nt - 1) / (4 * p.nt), base = n_groups * m_groups;
     // One workgroup per CU (256 CUs).  Few tiles: split k so that one round of workgroups covers the chip.
     // Many tiles: split k only if filling the last round pays for writing and re-reading the extra partial tiles.
@@ -320,6 +327,8 @@ void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int 
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
     if (Opk)
         gemm_kernel<2, true><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, Opk);
+    else if (plan.nt == 3)
+        gemm_kernel<3, false><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, nullptr);
     else if (plan.nt == 2)
         gemm_kernel<2, false><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, nullptr);
     else

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 def bb():
     from paper_2605_29233_amd import BlockBatch, Limits
     shape = ModelShape("gemmtest", 1, 1024, 8, 8, 128, 2752, 4096)
-    b = BlockBatch(shape, DecodeParams(), Limits(1, 2, 512, 128, 256))
+    b = BlockBatch(shape, DecodeParams(), Limits(1, 3, 512, 128, 256))
     yield b
     b.close()
 
@@ -30,6 +30,7 @@ def test_generator_is_bit_identical_on_gpu():
     (32, 32, 16, 1), (1, 64, 32, 1), (56, 768, 256, 0), (120, 1376, 256, 0), (37, 256, 688, 0),
     (130, 1024, 256, 0), (128, 4096, 1024, 1), (120, 1024, 2752, 0), (120, 1024, 2752, 3),
     (200, 2752, 1024, 2), (300, 96, 4096, 7),
+    (1536, 5632, 128, 0),          # 12 row groups x 176 column tiles: the plan takes 384-column tiles here
 ])
 def test_mfma_gemm_matches_fp64(bb, M, N, K, split):
     rng = np.random.default_rng(M * 7 + N)
