@@ -26,7 +26,7 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # by what the counter reads for a plain 16-byte-per-lane copy of known size (FETCH_SIZE x 2.000, WRITE_SIZE x
 # 1.000); the per-kernel table and the commands are in profiles/llada_hbm_traffic_pmc.md.  Counters cannot be
 # read from inside this process, so the figure is the stored one for the workload it was measured on.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"llada": 150.7e6}
+GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"llada": 152.8e6}
 
 
 def main():
