@@ -90,7 +90,7 @@ typedef struct {
     long rows, cols;
 } bb_tensor;
 
-/* Per-branch state S_k (Alg. 1 line 4) plus the counters Alg. 2 keeps. */
+/* Per-branch state S_k (Alg. 1, initialisation) plus the counters Alg. 2 keeps. */
 typedef struct {
     int block;              /* b_k                                                          */
     int start, end;         /* current window, absolute positions                           */
@@ -145,7 +145,7 @@ const char* bb_last_error(const bb_ctx* ctx);
  * released.  Every tensor must have been loaded before the first forward. */
 int bb_load_weights(bb_ctx* ctx, const bb_tensor* tensors, int n);
 
-/* Alg. 1 lines 1-4: X_k = prompt + G masks for each of the N branches, windows at the end of
+/* Alg. 1, initialisation: X_k = prompt + G masks for each of the N branches, windows at the end of
  * the prompt.  prompt_host: L_p token ids; block_sizes_host: N block sizes. */
 int bb_request_open(bb_ctx* ctx, const int32_t* prompt_host, int L_p, int G,
                     const int* block_sizes_host, int N, int* req_id_out);

@@ -5,8 +5,8 @@ block-size branch), the branch states, one K,V cache row per branch and each bra
 probability map P_k(i, .) of its own latest distributions.  The three phases mirror the
 library boundary so a test can drive both side by side:
 
-  init_forward()  / refresh()   full-sequence forward(s)            (Alg. 1 lines 5 and 12)
-  block_forward()               one batched block forward           (lines 15-17)
+  init_forward()  / refresh()   full-sequence forward(s)            (Alg. 1: InitialFullForward, RefreshIfNeeded)
+  block_forward()               one batched block forward           (Alg. 1: pack + BatchedBlockForward)
   commit_merge()                decode, map update, advance, MergeSync, refresh cadence
 
 Batching is execution shape only (Sec. 5.1: every branch owns a sequence row and a cache

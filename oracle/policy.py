@@ -77,7 +77,7 @@ def realign_window(X, br, L_p, L, mask_id):
 
 
 def pick_leader(X, branches, L_p, mask_id, leader_rule):
-    """rule 0 (Alg. 2 line 1): most tokens decoded, ties -> higher mean confidence -> lower
+    """rule 0 (Alg. 2, leader selection): most tokens decoded, ties -> higher mean confidence -> lower
     index.  rule 1 (tiny workload): highest mean confidence, ties -> lower index."""
     def key(br):
         td = tokens_decoded(X, br.k, L_p, mask_id)
