@@ -63,6 +63,7 @@ def test_tiny_full_trajectory():
     (5, (4, 8, 16, 32, 64), 100, 128, DecodeParams(0.9, 0.5, 8, 8, 0)),
     (6, (4, 8, 16, 32, 64, 128), 90, 256, DecodeParams(0.9, 0.5, 8, 32, 0)),   # the paper's six-branch setting (App. E.3)
     (7, (32,), 64, 96, DecodeParams(0.9, 0.5, 8, 8, 0)),               # one branch, one block size
+    (8, (1, 2, 4, 8, 16, 32, 64, 128), 41, 128, DecodeParams(0.9, 0.5, 8, 16, 0)),   # the maximum of 8 branches, block size 1
 ])
 def test_tiny_variants(seed, blocks, prompt_len, gen_len, decode):
     w = workload("tiny")
@@ -283,5 +284,14 @@ def test_error_paths():
         bb.merge_commit([r])
         bb.denoise_step([r])                         # and the context still works after the rejected calls
         assert bb.merge_commit([r])[0].nfe_block == 1
+        # a step over a request with nothing left to decode is an empty batch: no rows, state unchanged
+        r2 = bb.request_open(p, 64, w.block_sizes)
+        st = bb.generate([r2])[0]
+        assert st.finished == 1
+        X = bb.get_tokens(r2).copy()
+        view = bb.denoise_step([r2])
+        assert view.m_q == 0 and view.m_lm == 0
+        st2 = bb.merge_commit([r2])[0]
+        assert st2.finished == 1 and st2.winner == st.winner and np.array_equal(bb.get_tokens(r2), X)
     finally:
         bb.close()
