@@ -8,15 +8,16 @@
 //            row's pages round robin, each keeping a running max / sum / output (online
 //            softmax), and the partial results are combined through LDS in a fixed order;
 //   SPLITQ = true  (full-sequence refresh: many query rows): four tiles per workgroup, one per
-//            wave; the waves walk the pages together so K/V are fetched once per workgroup.
+//            wave; the waves walk the pages together, so the fragments the first wave pulls
+//            into L2 serve the other three.
 // Either way the result does not depend on scheduling.
 //
 // Q, K, V and the probabilities P each enter as two fp16 terms (hi + lo); every product keeps
 // the three leading cross terms (hi.hi + lo.hi + hi.lo), i.e. ~22 bits per operand.
 //
 // MFMA use (fp16 inputs, fp32 accumulate, 32x32x16):
-//   S^T[key][query]  = K[key][:] . Q[query][:]      A = K rows (as stored), B = Q rows
-//   O^T[d][query]   += V^T[d][key] . P^T[key][query] A = V^T (cache is stored transposed),
+//   S^T[key][query]  = K[key][:] . Q[query][:]      A = K fragments (the cache stores them ready-made), B = Q rows
+//   O^T[d][query]   += V^T[d][key] . P^T[key][query] A = V^T fragments (likewise),
 //                                                    B = P taken straight from the S^T
 //                                                    accumulators (same lane owns the same
 //                                                    query), keys permuted consistently.
