@@ -249,13 +249,39 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
         }
     }
     __syncthreads();
-    for (int it = t; it < 128 * 16; it += 256) {
-        const int c = it / 16, r = it % 16, m = m0 + r;
-        if (m >= count) continue;
-        const int e = c0 + c - nq - nk, head = e / hd, dd = e % hd;
-        const int pos = D.row_pos[m], tt = pos % BB_PAGE;
-        half_t* blk = D.Vt + kv_block_off(D, layer, D.row_phys[m], pos / BB_PAGE, head);
-        put2(blk + v_slot(tt, dd, 0), blk + v_slot(tt, dd, 1), tile[c][r]);
+    // Eight consecutive tokens of one head dim are one 16-byte piece of a V fragment.  Where the 8 rows of a
+    // half tile are such a run (positions p .. p+7 with p % 8 == 0 in one cache row: always in a refresh, and
+    // for block sizes that are multiples of 8) one thread stores the piece whole; otherwise element by element.
+    for (int g8 = 0; g8 < 2; ++g8) {
+        const int ma = m0 + 8 * g8;
+        if (ma >= count) break;
+        const int pa = D.row_pos[ma];
+        const bool run = ma + 7 < count && (pa & 7) == 0 && D.row_pos[ma + 7] == pa + 7 && D.row_phys[ma + 7] == D.row_phys[ma] &&
+                         D.row_gbr[ma + 7] == D.row_gbr[ma];
+        if (run) {
+            if (t < 128) {
+                const int c = t, e = c0 + c - nq - nk, head = e / hd, dd = e % hd, tt = pa % BB_PAGE;
+                half_t* blk = D.Vt + kv_block_off(D, layer, D.row_phys[ma], pa / BB_PAGE, head);
+                typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+                f16x8 hi, lo;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const float y = tile[c][8 * g8 + j];
+                    hi[j] = (half_t)y; lo[j] = (half_t)(y - (float)hi[j]);
+                }
+                *reinterpret_cast<f16x8*>(blk + v_slot(tt, dd, 0)) = hi;
+                *reinterpret_cast<f16x8*>(blk + v_slot(tt, dd, 1)) = lo;
+            }
+        } else {
+            for (int it = t; it < 128 * 8; it += 256) {
+                const int c = it / 8, r = 8 * g8 + it % 8, m = m0 + r;
+                if (m >= count) continue;
+                const int e = c0 + c - nq - nk, head = e / hd, dd = e % hd;
+                const int pos = D.row_pos[m], tt = pos % BB_PAGE;
+                half_t* blk = D.Vt + kv_block_off(D, layer, D.row_phys[m], pos / BB_PAGE, head);
+                put2(blk + v_slot(tt, dd, 0), blk + v_slot(tt, dd, 1), tile[c][r]);
+            }
+        }
     }
 }
 
