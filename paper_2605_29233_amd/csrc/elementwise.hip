@@ -153,9 +153,83 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restr
     }
 }
 
+// The same for many rows (full-sequence passes), eight consecutive rows per workgroup: the eight rows' pieces
+// of one 8-column group are adjacent in the packed panel, so a thread stores 128 contiguous bytes per term
+// instead of eight workgroups storing 16 bytes each.  d <= 4096 (two column groups per thread).
+__global__ __launch_bounds__(256) void rmsnorm_pack8_kernel(Dev D, float* __restrict__ h, const float* __restrict__ partial,
+                                                            int n_partial, size_t partial_stride,
+                                                            const float* __restrict__ gain, u32x4* __restrict__ Apk, int mt_total) {
+    constexpr int R = 8, G = 2;
+    __shared__ float sh[4][R];
+    const int j0 = blockIdx.x * R, d = D.d, k8s = d >> 3, count = D.counts[0], t = threadIdx.x;
+    float v[R][G][8], ss[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        ss[r] = 0.f;
+        const int j = j0 + r;
+        float* hr = h + (size_t)j * d;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const int k8 = t + 256 * i;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) v[r][i][q] = 0.f;
+            if (j < count && k8 < k8s) {
+                const float4 a = reinterpret_cast<const float4*>(hr)[2 * k8], b = reinterpret_cast<const float4*>(hr)[2 * k8 + 1];
+                float4 p[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
+                if (n_partial) {
+                    const size_t off[2] = {(size_t)j * d + k8 * 8, (size_t)j * d + k8 * 8 + 4};
+                    part_sum4n<2>(partial, n_partial, partial_stride, off, p);
+                }
+                v[r][i][0] = a.x + p[0].x; v[r][i][1] = a.y + p[0].y; v[r][i][2] = a.z + p[0].z; v[r][i][3] = a.w + p[0].w;
+                v[r][i][4] = b.x + p[1].x; v[r][i][5] = b.y + p[1].y; v[r][i][6] = b.z + p[1].z; v[r][i][7] = b.w + p[1].w;
+                if (n_partial) {
+                    reinterpret_cast<float4*>(hr)[2 * k8] = make_float4(v[r][i][0], v[r][i][1], v[r][i][2], v[r][i][3]);
+                    reinterpret_cast<float4*>(hr)[2 * k8 + 1] = make_float4(v[r][i][4], v[r][i][5], v[r][i][6], v[r][i][7]);
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) ss[r] += v[r][i][q] * v[r][i][q];
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        for (int o = 32; o > 0; o >>= 1) ss[r] += __shfl_xor(ss[r], o, 64);
+        if ((t & 63) == 0) sh[t >> 6][r] = ss[r];
+    }
+    __syncthreads();
+    float inv[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) inv[r] = 1.0f / sqrtf((sh[0][r] + sh[1][r] + sh[2][r] + sh[3][r]) / (float)d + D.rms_eps);
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        const int k8 = t + 256 * i;
+        if (k8 >= k8s) break;
+        const float4 g0 = reinterpret_cast<const float4*>(gain)[2 * k8], g1 = reinterpret_cast<const float4*>(gain)[2 * k8 + 1];
+        const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+        for (int term = 0; term < 2; ++term)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {           // rows past the count hold zeros
+                uint16_t o16[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const float y = v[r][i][q] * inv[r] * gg[q];
+                    const uint16_t hi = f32_to_bf16_rne(y);
+                    o16[q] = term == 0 ? hi : f32_to_bf16_rne(y - bf16_to_f32(hi));
+                }
+                Apk[packA_u4(j0 + r, k8, mt_total, term)] = *reinterpret_cast<u32x4*>(o16);
+            }
+    }
+}
+
 void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
                          const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, hipStream_t s) {
-    rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, gather, bcast);
+    // eight rows per workgroup once that still gives every CU a workgroup, or when a row is too short to occupy
+    // one (d <= 512: at most 64 of the 256 threads have a column group)
+    if (!gather && D.d <= 4096 && mt_total * 32 > 256 && (mt_total * 4 >= 256 || D.d <= 512))
+        rmsnorm_pack8_kernel<<<mt_total * 4, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total);
+    else
+        rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, gather, bcast);
 }
 
 static __device__ __forceinline__ void put2(half_t* hi_p, half_t* lo_p, float y) {
