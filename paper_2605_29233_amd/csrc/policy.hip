@@ -35,40 +35,58 @@ static __device__ __forceinline__ float wg_sum_f(float v, float* sh) {
 __global__ __launch_bounds__(256) void pack_step_kernel(Dev D, int n_req) {
     __shared__ int s_rows[256], s_lm[256], s_off[257], s_lmoff[257];
     const int nb_all = D.max_req * D.max_br, nb = n_req * D.max_br, t = threadIdx.x;
+    const int wave = t >> 6, lane = t & 63;
     for (int i = t; i < nb_all; i += 256) D.seg_rows[i] = 0;
     if (t == 0) D.counts[2] = 0;
+    for (int i = t; i < 256; i += 256) { s_rows[i] = 0; s_lm[i] = 0; }
     __syncthreads();
-    int slot = 0, k = 0, rows = 0, nlm = 0, start = 0, end = 0;
-    const int* Xr = nullptr;
-    if (t < nb) {
-        slot = D.req_list[t / D.max_br]; k = t % D.max_br;
+    // one wave per branch (round robin): window length and number of masked positions
+    for (int b = wave; b < nb; b += 4) {
+        const int slot = D.req_list[b / D.max_br], k = b % D.max_br;
         const ReqHeader& H = D.hdr[slot];
         const bb_branch_state& B = D.br[slot * D.max_br + k];
+        int rows = 0, nlm = 0;
         if (k < H.N && !B.done) {
-            start = B.start; end = B.end; rows = end - start;
-            Xr = D.X + ((size_t)slot * D.max_br + k) * D.lpad;
-            for (int i = start; i < end; ++i) nlm += Xr[i] == D.mask_id;
+            const int start = B.start, end = B.end;
+            rows = end - start;
+            const int* Xr = D.X + ((size_t)slot * D.max_br + k) * D.lpad;
+            for (int i = start + lane; i < end; i += 64) nlm += Xr[i] == D.mask_id;
+            for (int o = 32; o > 0; o >>= 1) nlm += __shfl_xor(nlm, o, 64);
         }
-        D.hdr[slot].pending[k] = rows > 0;
+        if (lane == 0) { s_rows[b] = rows; s_lm[b] = nlm; D.hdr[slot].pending[k] = rows > 0; }
     }
-    s_rows[t] = rows; s_lm[t] = nlm;
     __syncthreads();
     if (t == 0) {
-        int a = 0, b = 0;
-        for (int i = 0; i < nb; ++i) { s_off[i] = a; s_lmoff[i] = b; a += s_rows[i]; b += s_lm[i]; }
-        D.counts[0] = a; D.counts[1] = b;
+        int a = 0, c = 0;
+        for (int i = 0; i < nb; ++i) { s_off[i] = a; s_lmoff[i] = c; a += s_rows[i]; c += s_lm[i]; }
+        D.counts[0] = a; D.counts[1] = c;
     }
     __syncthreads();
-    if (t < nb && rows > 0) {
+    for (int b = wave; b < nb; b += 4) {
+        const int rows = s_rows[b];
+        if (rows == 0) continue;
+        const int slot = D.req_list[b / D.max_br], k = b % D.max_br;
+        const bb_branch_state& B = D.br[slot * D.max_br + k];
+        const int start = B.start, end = B.end;
         const int gbr = slot * D.max_br + k, own = slot * D.phys_per_req + k;
-        D.seg_off[gbr] = s_off[t]; D.seg_rows[gbr] = rows;
-        int c = s_lmoff[t];
-        for (int i = start; i < end; ++i) {
-            const int r = s_off[t] + (i - start);
-            D.row_tok[r] = Xr[i]; D.row_pos[r] = i; D.row_gbr[r] = gbr; D.row_phys[r] = own;
-            if (Xr[i] == D.mask_id) D.lm_row[c++] = r;
+        const int* Xr = D.X + (size_t)gbr * D.lpad;
+        if (lane == 0) { D.seg_off[gbr] = s_off[b]; D.seg_rows[gbr] = rows; }
+        int c = s_lmoff[b];                          // LM rows keep the order of the positions
+        for (int i0 = start; i0 < end; i0 += 64) {
+            const int i = i0 + lane;
+            const bool in = i < end;
+            const int tok = in ? Xr[i] : 0;
+            const bool masked = in && tok == D.mask_id;
+            const unsigned long long bal = __ballot(masked);
+            if (in) {
+                const int r = s_off[b] + (i - start);
+                D.row_tok[r] = tok; D.row_pos[r] = i; D.row_gbr[r] = gbr; D.row_phys[r] = own;
+                if (masked) D.lm_row[c + __popcll(bal & ((1ull << lane) - 1))] = r;
+            }
+            c += __popcll(bal);
         }
-        for (int p = start / BB_PAGE; p <= (end - 1) / BB_PAGE; ++p) {
+        // pages under the window that the branch does not own yet: queue a copy-on-write and re-point
+        for (int p = start / BB_PAGE + lane; p <= (end - 1) / BB_PAGE; p += 64) {
             int* e = &D.table[(size_t)gbr * D.n_pages + p];
             if (*e != own) {
                 const int idx = atomicAdd(&D.counts[2], 1);
@@ -334,7 +352,7 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
                 if (s == d) { if (t == 0) S.compat[s] = 0; continue; }
                 const int* Xs = X + (size_t)s * D.lpad;
                 int bad = 0;
-                for (int i = t; i < L; i += 256) bad += Xs[i] != mask && Xd[i] != mask && Xs[i] != Xd[i];
+                for (int i = L_p + t; i < L; i += 256) bad += Xs[i] != mask && Xd[i] != mask && Xs[i] != Xd[i];   // prompt rows are equal
                 bad = wg_sum_i(bad, S.si);
                 if (t == 0) S.compat[s] = bad == 0;
                 if (bad == 0) { lo = min(lo, B[s].start); hi = max(hi, B[s].end); }
