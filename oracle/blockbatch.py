@@ -17,7 +17,7 @@ import numpy as np
 
 from .model import OracleModel, softmax_rows, confidence_argmax
 from .policy import (Branch, decode_current_block, advance_block, merge_sync, tokens_decoded, check_eos,
-                     select_winner)
+                     select_winner, PAPER)
 
 
 @dataclass
@@ -124,7 +124,7 @@ class OracleRequest:
             self.V[dst][i][:] = self.V[src][i]
         self.P[dst] = self.P[src]
 
-    def decode_all(self):
+    def decode_all(self, cmp=PAPER):
         """DecodeCurrentBlock (Eq. 1) + UpdateProbabilityMap for every branch that received logits."""
         r, p = self.pending, self.p
         commits = []
@@ -134,7 +134,7 @@ class OracleRequest:
             if len(sel) == 0 or br.done:
                 continue
             commits += [(br.k, i) for i in decode_current_block(
-                self.X, br, r.pos[sel], r.conf[sel], r.pred[sel], p.tau_dec, self.mask_id)]
+                self.X, br, r.pos[sel], r.conf[sel], r.pred[sel], p.tau_dec, self.mask_id, cmp)]
             self.P[br.k, r.pos[sel] - self.L_p] = probs[sel]
         self.pending = None
         return commits
@@ -143,21 +143,22 @@ class OracleRequest:
         for br in self.br:
             advance_block(self.X, br, self.L, self.mask_id)
 
-    def merge_sync_all(self, prob=None):
+    def merge_sync_all(self, prob=None, cmp=PAPER, copy_row=None):
         prob = prob or (lambda d, i, v: self.P[d, i - self.L_p, v])
         return merge_sync(self.X, self.br, prob, self.L_p, self.L, self.mask_id,
-                          self.p.tau_merge, self.p.tau_sync, self.p.leader_rule, self._copy_row)
+                          self.p.tau_merge, self.p.tau_sync, self.p.leader_rule, copy_row or self._copy_row, cmp)
 
-    def commit_merge(self):
-        """DecodeCurrentBlock + UpdateProbabilityMap per branch, AdvanceCompletedBlocks,
-        MergeSync, and the refresh cadence (a refresh is due once R block forwards have run
-        since the last one).  Returns a dict of what happened."""
+    def commit_merge(self, cmp=PAPER, copy_row=None):
+        """DecodeCurrentBlock + UpdateProbabilityMap per branch, CheckEOS (inside the loop of Alg. 1
+        only), AdvanceCompletedBlocks, MergeSync, and the refresh cadence (a refresh is due once R
+        block forwards have run since the last one).  Returns a dict of what happened.
+        cmp / copy_row: see policy.PaperComparisons and policy.merge_sync (tests only)."""
         decoded_now = self.decoded_branches()
-        commits = self.decode_all()
+        commits = self.decode_all(cmp)
         if self.eos_finish(decoded_now):
             return {"commits": commits, "merges": [], "syncs": [], "refresh_due": False}
         self.advance_all()
-        merges, syncs = self.merge_sync_all()
+        merges, syncs = self.merge_sync_all(cmp=cmp, copy_row=copy_row)
         self.end_of_commit()
         return {"commits": commits, "merges": merges, "syncs": syncs, "refresh_due": self.refresh_due}
 
@@ -169,7 +170,12 @@ class OracleRequest:
 
     def eos_finish(self, decoded_now):
         """CheckEOS for the branches that were just decoded; an EOS-ready branch ends the request
-        (SelectEOSWinner), before AdvanceCompletedBlocks and MergeSync as in Alg. 1."""
+        (SelectEOSWinner), before AdvanceCompletedBlocks and MergeSync as in Alg. 1.  Alg. 1 has
+        CheckEOS only in the body of its while loop: the decode that follows InitialFullForward is
+        not followed by one, so a branch that is EOS-ready right after the initial commit is
+        noticed by the first loop iteration that decodes it."""
+        if self.nfe["block"] == 0:
+            return False
         ready = [k for k in decoded_now if check_eos(self.X, k, self.L_p, self.eos_id, self.mask_id)[1]]
         if not ready:
             return False

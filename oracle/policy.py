@@ -8,6 +8,28 @@ from dataclasses import dataclass, field
 import numpy as np
 
 
+class PaperComparisons:
+    """Every floating-point decision the policy takes, exactly as the paper prints it: Eq. 1 commits
+    at c >= tau_dec, Alg. 2 accepts a merge at p > tau_conf, and the arg max of Eq. 1 (i*), of the
+    merge step (s*) and of the leader selection take the first maximum in the order given.
+    The policy functions below route those decisions through an object of this class so that a test
+    can learn which of them sit within rounding distance of flipping (it passes a subclass that
+    records or overrides them); the default object is the literal rule and nothing else.  `what`
+    names the decision (a tuple such as ("commit", branch, position)) and is ignored here."""
+
+    def at_least(self, c, tau, what=None):
+        return bool(c >= tau)
+
+    def exceeds(self, p, tau, what=None):
+        return bool(p > tau)
+
+    def first_max(self, values, what=None):
+        return int(np.argmax(np.asarray(values, dtype=np.float64)))      # numpy: first maximum
+
+
+PAPER = PaperComparisons()
+
+
 @dataclass
 class Branch:
     """Branch state S_k of Alg. 1: index, block size, current window [start, end), done flag."""
@@ -30,7 +52,7 @@ def tokens_decoded(X, k, L_p, mask_id):
     return int(np.count_nonzero(X[k, L_p:] != mask_id))
 
 
-def decode_current_block(X, br, rows, conf, pred, tau_dec, mask_id):
+def decode_current_block(X, br, rows, conf, pred, tau_dec, mask_id, cmp=PAPER):
     """Eq. 1 on branch br's window.  rows: positions that were masked when the forward ran
     (ascending); conf/pred: their top-1 confidence and token.  A masked position commits its
     argmax token if conf >= tau_dec or it is i*, the most confident masked position
@@ -38,14 +60,15 @@ def decode_current_block(X, br, rows, conf, pred, tau_dec, mask_id):
     if len(rows) == 0:
         return []
     conf = np.asarray(conf, dtype=np.float64)
-    istar = int(np.argmax(conf))            # first maximum = lowest position
+    istar = cmp.first_max(conf, ("istar", br.k))            # first maximum = lowest position
     out = []
     for j, i in enumerate(rows):
         assert X[br.k, i] == mask_id
-        if conf[j] >= tau_dec or j == istar:
+        passes = cmp.at_least(conf[j], tau_dec, ("commit", br.k, int(i)))
+        if passes or j == istar:
             X[br.k, i] = pred[j]
             out.append(int(i))
-            if conf[j] >= tau_dec:
+            if passes:
                 br.committed_threshold += 1
             else:
                 br.committed_fallback += 1
@@ -76,13 +99,14 @@ def realign_window(X, br, L_p, L, mask_id):
     br.done = False
 
 
-def pick_leader(X, branches, L_p, mask_id, leader_rule):
+def pick_leader(X, branches, L_p, mask_id, leader_rule, cmp=PAPER):
     """rule 0 (Alg. 2, leader selection): most tokens decoded, ties -> higher mean confidence -> lower
     index.  rule 1 (tiny workload): highest mean confidence, ties -> lower index."""
-    def key(br):
-        td = tokens_decoded(X, br.k, L_p, mask_id)
-        return (-td, -br.mean_conf, br.k) if leader_rule == 0 else (-br.mean_conf, br.k)
-    return min(branches, key=key)
+    cands = list(branches)                       # index order, so a first maximum is the lowest index
+    if leader_rule == 0:
+        td = [tokens_decoded(X, br.k, L_p, mask_id) for br in cands]
+        cands = [br for br, t in zip(cands, td) if t == max(td)]
+    return cands[cmp.first_max([br.mean_conf for br in cands], ("leader",) + tuple(br.k for br in cands))]
 
 
 def check_eos(X, k, L_p, eos_id, mask_id):
@@ -111,14 +135,14 @@ def compatible(X, s, d, mask_id):
     return bool(np.all(X[s][both] == X[d][both]))
 
 
-def merge_sync(X, branches, prob, L_p, L, mask_id, tau_merge, tau_sync, leader_rule, copy_row):
+def merge_sync(X, branches, prob, L_p, L, mask_id, tau_merge, tau_sync, leader_rule, copy_row, cmp=PAPER):
     """Alg. 2.  prob(d, i, v) -> P_d(i, v), the destination's own probability of token v at
     position i; copy_row(src, dst) copies cache row and probability map (sync).
     Returns (merges [(d, i, v, s)], syncs [(d, leader)])."""
     merges, syncs = [], []
     for br in branches:
         br.synced_from = -1
-    lead = pick_leader(X, branches, L_p, mask_id, leader_rule)
+    lead = pick_leader(X, branches, L_p, mask_id, leader_rule, cmp)
     if tokens_decoded(X, lead.k, L_p, mask_id) == 0:
         return merges, syncs
     # active = not done; most advanced first, index breaks ties
@@ -136,8 +160,8 @@ def merge_sync(X, branches, prob, L_p, L, mask_id, tau_merge, tau_sync, leader_r
             if not cands:
                 continue
             ps = [prob(d.k, i, int(X[s.k, i])) for s in cands]
-            j = int(np.argmax(ps))      # first maximum = earliest source in the order
-            if ps[j] > tau_merge:
+            j = cmp.first_max(ps, ("merge_source", d.k, int(i)))      # first maximum = earliest source in the order
+            if cmp.exceeds(ps[j], tau_merge, ("merge_accept", d.k, int(i))):
                 X[d.k, i] = X[cands[j].k, i]
                 d.tokens_merged += 1
                 merges.append((d.k, int(i), int(X[d.k, i]), cands[j].k))

@@ -22,6 +22,8 @@ M = 99      # mask id used by the hand-made cases
     ([0.3, 0.5, 0.4], [1]),                    # nothing passes: only i*
     ([0.5, 0.5, 0.1], [0]),                    # tie for i* -> lowest position
     ([0.9, 0.1], [0]),                         # c == tau commits (>=)
+    ([0.95, 0.9], [0, 1]),                     # c == tau on a row that is not i*: only ">=" commits it
+    ([0.95, 0.8999999], [0]),                  # just below tau and not i*: stays masked
     ([0.8999999, 0.95], [1]),
 ])
 def test_commit_rule_enumeration(conf, expect):
@@ -97,6 +99,32 @@ def test_merge_sync_golden(case):
     assert [list(s) for s in syncs] == case["expect_syncs"]
     assert copies == [(l, d) for d, l in syncs]           # cache row + map copied leader -> laggard
     assert len(merges) == sum(case["expect_merged"])
+    if "expect_mean_conf" in case:
+        assert [b.mean_conf for b in brs] == case["expect_mean_conf"]
+
+
+def test_mean_confidence_copied_by_a_sync_decides_the_next_leader():
+    """Hand-derived, leader rule 1 (highest mean confidence, lower index on ties).  Pass 1: branch 1
+    (complete row, 0.8) leads; branch 0 lags by 4 > tau_sync = 2 and receives row 1, which finishes
+    it; branch 2 lags by exactly 2 and is left alone.  The copy brings the leader's mean confidence
+    along, so the next pick sees 0.8 / 0.8 / 0.5 and takes branch 0 (lower index); had the laggard
+    kept its own 0.1 the leader would still be branch 1.  Pass 2 (tau_sync = 0) shows it: branch 2
+    is copied from branch 0."""
+    from oracle.policy import pick_leader
+    L_p, L = 1, 5
+    X = np.array([[42, M, M, M, M], [42, 1, 2, 3, 4], [42, 1, 2, M, M]])
+    brs = [Branch(0, 4, 1, 5, mean_conf=0.1), Branch(1, 4, 5, 5, done=True, mean_conf=0.8), Branch(2, 4, 1, 5, mean_conf=0.5)]
+    copies = []
+    prob = lambda d, i, v: 0.0
+    merges, syncs = merge_sync(X, brs, prob, L_p, L, M, 0.5, 2, 1, lambda s, d: copies.append((s, d)))
+    assert merges == [] and syncs == [(0, 1)] and copies == [(1, 0)]
+    assert X.tolist() == [[42, 1, 2, 3, 4], [42, 1, 2, 3, 4], [42, 1, 2, M, M]]
+    assert (brs[0].done, brs[0].start, brs[0].end, brs[0].synced_from) == (True, 5, 5, 1)
+    assert [b.mean_conf for b in brs] == [0.8, 0.8, 0.5]
+    assert pick_leader(X, brs, L_p, M, 1) is brs[0]
+    merges, syncs = merge_sync(X, brs, prob, L_p, L, M, 0.5, 0, 1, lambda s, d: copies.append((s, d)))
+    assert syncs == [(2, 0)] and copies == [(1, 0), (0, 2)]
+    assert X[2].tolist() == [42, 1, 2, 3, 4] and brs[2].done and brs[2].synced_from == 0
 
 
 # ---- driver-level special cases and invariants ----------------------------------------------
@@ -306,3 +334,51 @@ def test_eos_run_matches_plain_run_until_it_stops(tiny):
     assert not np.any(row[rq.L_p:rq.eos_pos] == rq.mask_id)
     assert rq.all_done() and not rq.refresh_due
     # the step before, no decoded branch was ready
+
+
+# ---- CheckEOS sits inside the loop of Alg. 1 only ------------------------------------------------------
+class _TableModel:
+    """Stand-in for the network: logits are a fixed table indexed by position (no weights, no cache use)."""
+
+    class _Shape:
+        n_layers, d_model, vocab, mask_id = 1, 1, 6, 5
+
+    def __init__(self, table):
+        self.s, self.table = self._Shape(), table
+
+    def new_cache(self, L):
+        return [np.zeros((L, 1, 1))], [np.zeros((L, 1, 1))]
+
+    def forward_rows(self, tokens, pos, K, V, L, want_hidden=True):
+        return np.asarray(pos, dtype=np.float64)[:, None] if want_hidden else None
+
+    def logits(self, h):
+        lg = np.array([self.table[int(p)] for p in h[:, 0]], dtype=np.float64)
+        lg[:, self.s.mask_id] = -np.inf
+        return lg
+
+
+def test_eos_ready_after_the_initial_commit_is_noticed_by_the_first_loop_iteration():
+    """Alg. 1 runs CheckEOS inside its while loop only: DecodeCurrentBlock after InitialFullForward is
+    followed by AdvanceCompletedBlocks and MergeSync, not by CheckEOS.  Hand case (EOS = 4, mask = 5,
+    L_p = 2, G = 4, blocks 2 and 4, tau_dec 0.9): position 2 predicts EOS with confidence
+    e^10 / (e^10 + 4) > 0.9, so both branches commit it in the initial decode and are EOS-ready at
+    once (empty prefix), yet the request keeps running; the first block forward commits one more
+    token per branch (i*: position 3 for branch 0, position 4 with e^2 / (e^2 + 4) for branch 1),
+    CheckEOS then fires and the winner is branch 0 (both hold 2 tokens, lowest index)."""
+    E = 4
+    table = {2: [0, 0, 0, 0, 10, 0], 3: [0, 1, 0, 0, 0, 0], 4: [0, 0, 2, 0, 0, 0], 5: [0, 0, 0, 0.5, 0, 0],
+             0: [0] * 6, 1: [0] * 6}
+    p = DecodeParams(tau_dec=0.9, tau_merge=0.5, tau_sync=8, refresh_interval=100, leader_rule=0, eos_id=E)
+    rq = OracleRequest(_TableModel(table), [0, 1], 4, (2, 4), p)
+    rq.init_forward()
+    info = rq.commit_merge()
+    assert sorted(info["commits"]) == [(0, 2), (1, 2)]
+    assert rq.X.tolist() == [[0, 1, E, 5, 5, 5], [0, 1, E, 5, 5, 5]]
+    assert rq.finished == 0 and rq.winner == -1 and not rq.all_done()        # ready, but nobody looked
+    rq.block_forward()
+    info = rq.commit_merge()
+    assert sorted(info["commits"]) == [(0, 3), (1, 4)]
+    assert rq.X.tolist() == [[0, 1, E, 1, 5, 5], [0, 1, E, 5, 2, 5]]
+    assert (rq.finished, rq.winner, rq.eos_pos) == (2, 0, 2) and rq.all_done()
+    assert rq.nfe == {"init": 1, "block": 1, "refresh": 0}
