@@ -60,7 +60,7 @@ def decode_current_block(X, br, rows, conf, pred, tau_dec, mask_id, cmp=PAPER):
     if len(rows) == 0:
         return []
     conf = np.asarray(conf, dtype=np.float64)
-    istar = cmp.first_max(conf, ("istar", br.k))            # first maximum = lowest position
+    istar = cmp.first_max(conf, ("istar", br.k, tuple(int(i) for i in rows)))     # first maximum = lowest position
     out = []
     for j, i in enumerate(rows):
         assert X[br.k, i] == mask_id
@@ -160,7 +160,8 @@ def merge_sync(X, branches, prob, L_p, L, mask_id, tau_merge, tau_sync, leader_r
             if not cands:
                 continue
             ps = [prob(d.k, i, int(X[s.k, i])) for s in cands]
-            j = cmp.first_max(ps, ("merge_source", d.k, int(i)))      # first maximum = earliest source in the order
+            # first maximum = earliest source in the order
+            j = cmp.first_max(ps, ("merge_source", d.k, int(i), tuple(int(X[s.k, i]) for s in cands)))
             if cmp.exceeds(ps[j], tau_merge, ("merge_accept", d.k, int(i))):
                 X[d.k, i] = X[cands[j].k, i]
                 d.tokens_merged += 1

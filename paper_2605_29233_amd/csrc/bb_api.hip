@@ -641,6 +641,8 @@ extern "C" int bb_set_state(bb_ctx* c, int id, const int32_t* X, const bb_branch
     HIPCHK(c, hipMemcpy(cur, c->D.br + id * c->D.max_br, sizeof(bb_branch_state) * c->D.max_br, hipMemcpyDeviceToHost));
     for (int k = 0; k < R.N; ++k) {
         if (brs[k].start < R.L_p || brs[k].end > R.L || brs[k].start > brs[k].end) return fail(c, BB_EINVAL, "window out of range");
+        // the forward's row lists are sized from the block sizes: a window never holds more than one block
+        if (brs[k].end - brs[k].start > std::min(R.blocks[k], R.G)) return fail(c, BB_EINVAL, "window wider than the branch's block");
         for (int i = 0; i < R.L; ++i)
             if (X[(size_t)k * R.L + i] < 0 || X[(size_t)k * R.L + i] >= c->m.vocab) return fail(c, BB_EINVAL, "token out of range");
         HIPCHK(c, hipMemcpy(c->D.X + ((size_t)id * c->D.max_br + k) * c->D.lpad, X + (size_t)k * R.L, R.L * 4, hipMemcpyHostToDevice));

@@ -277,7 +277,9 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
     // -- CheckEOS (Alg. 1) on the branches that were just decoded: the branch's EOS is the first generation
     //    position holding the EOS token, and it is EOS-ready when nothing before that is masked.  A ready
     //    branch ends the request (most tokens decoded wins, lowest index on ties) before advance / MergeSync.
-    if (D.eos_id >= 0) {
+    //    Alg. 1 has CheckEOS in the body of its while loop only: the commit that follows the initial full
+    //    forward (no block forward has run yet) skips it.
+    if (D.eos_id >= 0 && H.nfe_block > 0) {
         __syncthreads();
         if (t == 0) S.win = -1;
         for (int k = 0; k < N; ++k) {

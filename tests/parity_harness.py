@@ -1,22 +1,38 @@
 """Drives the CPU oracle and the HIP library side by side, teacher-forced.
 
-Before every GPU call the GPU token / window state equals the oracle's (it is overwritten with
-the oracle's after every commit).  Comparison bar:
-  * logits: max-abs <= 3e-2 over every row that received logits (mask column excluded);
-  * argmax, commit, merge, sync, window and done decisions: bit-exact unless the oracle itself
-    is within a guard band of flipping (top-1/top-2 logit margin, |c - tau_dec|, the two best
-    confidences when the fallback arm picks i*, |p - tau_merge|, competing merge candidates,
-    competing leaders: all 1e-2); such steps are counted as fragile, compared, and reported.
+Before every GPU call the token / window / counter state of the two sides is equal.  Comparison bar:
+  * logits: max-abs <= 3e-2 over every row that received logits (mask column excluded); top-1
+    confidence within 5e-3; argmax equal wherever the oracle's top-1 / top-2 logit margin exceeds 1e-2;
+  * commit, merge, sync, window, done, counter, EOS and winner results: bit-exact, decision by decision.
+    A floating-point decision of the oracle that lies within a guard band of flipping is allowed to fall
+    either way.  The band is 1e-2 for a value against a threshold (a confidence against tau_dec, a merge
+    probability against tau_merge), for competing merge sources and for an argmax over near-equal
+    logits; two confidences compared with each other (the arg max that picks i*, competing leaders'
+    mean confidences) can only swap if they are closer than twice the per-value tolerance that
+    the forward comparison asserts (conf_tol), so that is their band:
+    an in-band Eq. 1 decision (threshold, i*, argmax token) is taken the way the library's own reported
+    confidence / argmax of that row says (which also checks that its commits are consistent with what it
+    reports); for the remaining in-band decisions (leader, merge acceptance, merge source) the oracle's
+    policy is run once per combination ("worlds"; usually there is exactly one) and the GPU's complete
+    state after the commit must equal the complete state of one of them.  Everything a guard-band decision cannot reach is therefore asserted exactly, in every
+    step, and what it can reach must still be a consistent outcome of the algorithm.  When the GPU
+    took an in-band decision the other way, the oracle continues from that world (same tokens, same
+    cache-row copies), so both sides stay comparable without rewriting GPU state.
 """
+import copy
+from types import SimpleNamespace
+
 import numpy as np
 
 from oracle.model import OracleModel
-from oracle.blockbatch import OracleRequest
-from oracle.policy import tokens_decoded
+from oracle.blockbatch import OracleRequest, ForwardResult
+from oracle.policy import tokens_decoded, PaperComparisons
 from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT, BB_PERIODIC
 
 GUARD = 1e-2
 LOGIT_TOL = 3e-2
+CONF_TOL = 5e-3
+MAX_WORLDS = 256
 
 
 class Report:
@@ -25,25 +41,168 @@ class Report:
         self.max_conf_err = 0.0
         self.rows = 0
         self.steps = 0
-        self.fragile_steps = 0
-        self.fragile_mismatch = 0
+        self.commit_steps = 0           # commits compared (each one: complete state equal to an admissible outcome)
+        self.exact_steps = 0            # ... in which no decision at all was inside a guard band
+        self.asserted_steps = 0         # ... in which at least one decision was outside every band (asserted exactly)
+        self.decisions = 0              # floating-point decisions the oracle's policy took (Eq. 1 rows, i*, leader, merges)
+        self.in_band = 0                # ... of which inside a guard band (allowed to fall either way)
+        self.flipped = 0                # ... of which the GPU took the other way than the oracle's literal rule
+        self.max_worlds = 1             # most policy runs needed for one commit
         self.argmax_in_band = 0
         self.commits = self.merges = self.syncs = 0
 
     def __repr__(self):
         return (f"steps={self.steps} rows={self.rows} max_logit_err={self.max_logit_err:.3e} "
-                f"max_conf_err={self.max_conf_err:.3e} fragile_steps={self.fragile_steps} "
-                f"fragile_mismatch={self.fragile_mismatch} argmax_in_band={self.argmax_in_band} "
-                f"commits={self.commits} merges={self.merges} syncs={self.syncs}")
+                f"max_conf_err={self.max_conf_err:.3e} commit_steps={self.commit_steps} exact_steps={self.exact_steps} "
+                f"asserted_steps={self.asserted_steps} decisions={self.decisions} in_band={self.in_band} "
+                f"flipped={self.flipped} max_worlds={self.max_worlds} "
+                f"argmax_in_band={self.argmax_in_band} commits={self.commits} merges={self.merges} syncs={self.syncs}")
+
+
+class GuardedComparisons(PaperComparisons):
+    """The paper's comparisons, except that a decision within its guard band is a free choice.  Where what the
+    library did shows which way it took the decision (its reported confidence of the row, the token the
+    destination holds afterwards, the row a laggard was copied from) that way is tried; otherwise the choices are
+    taken from `prefix` in the order they come up (0 = the literal outcome) and recorded, so that the caller can
+    enumerate every combination.  Either way this only steers the search: the caller accepts a run only if the
+    complete resulting state equals the library's."""
+
+    def __init__(self, prefix, tau_dec, tau_merge, conf_band=GUARD, hints=None):
+        """hints: None, or an object with conf {(branch, position): reported confidence}, X (token rows after the
+        commit), synced_from [branch] and mask_id."""
+        self.prefix, self.taken, self.memo = list(prefix), [], {}
+        self.tau_dec, self.tau_merge, self.conf_band = tau_dec, tau_merge, conf_band
+        self.h = hints
+        self.decisions = self.in_band = self.flipped = 0
+
+    def choose(self, options, key=None):
+        """key: the compared values.  Two decisions on exactly the same values (rows of branches that hold the
+        same tokens) are one decision: the library produces identical bits for identical rows, so it cannot take
+        them differently; sharing the choice only narrows what is admitted."""
+        if key is not None and key in self.memo:
+            return options[self.memo[key]]
+        n = len(self.taken)
+        pick = self.prefix[n] if n < len(self.prefix) else 0
+        self.taken.append((pick, len(options)))
+        if key is not None:
+            self.memo[key] = pick
+        self.flipped += pick != 0
+        return options[pick]
+
+    def _hinted(self, nat, got):
+        self.flipped += got != nat
+        return got
+
+    def at_least(self, c, tau, what=None):
+        nat = bool(c >= tau)
+        self.decisions += 1
+        if abs(c - tau) > GUARD:
+            return nat
+        self.in_band += 1
+        if self.h is not None and what and what[0] == "commit" and (what[1], what[2]) in self.h.conf:
+            return self._hinted(nat, bool(self.h.conf[(what[1], what[2])] >= np.float32(tau)))
+        return self.choose([nat, not nat], ("ge", float(c), float(tau)))
+
+    def exceeds(self, p, tau, what=None):
+        nat = bool(p > tau)
+        self.decisions += 1
+        if abs(p - tau) > GUARD:
+            return nat
+        self.in_band += 1
+        if self.h is not None and what and what[0] == "merge_accept" and self.h.synced_from[what[1]] < 0:
+            return self._hinted(nat, bool(self.h.X[what[1], what[2]] != self.h.mask_id))
+        return self.choose([nat, not nat], ("gt", float(p), float(tau)))
+
+    def first_max(self, values, what=None):
+        v = np.asarray(values, dtype=np.float64)
+        nat = int(np.argmax(v))
+        kind = what[0] if what else None
+        self.decisions += 1
+        band = self.conf_band if kind in ("istar", "leader") else GUARD
+        alts = [j for j in range(len(v)) if j != nat and v[j] >= v[nat] - band]
+        if not alts:
+            return nat
+        # an i* that passes the threshold anyway, or a best source that cannot be accepted, decides nothing
+        if kind == "istar":
+            if min(v[j] for j in [nat] + alts) > self.tau_dec + GUARD:
+                return nat
+            self.in_band += 1
+            if self.h is not None and all((what[1], i) in self.h.conf for i in what[2]):
+                cands = sorted([nat] + alts)
+                g = [float(self.h.conf[(what[1], what[2][j])]) for j in cands]
+                return self._hinted(nat, cands[int(np.argmax(g))])      # first maximum = lowest position, as the kernel does
+        elif kind == "merge_source":
+            if v[nat] < self.tau_merge - GUARD:
+                return nat
+            # sources that offer the same token are one alternative (the token is what the destination takes)
+            toks, seen = what[3], {what[3][nat]}
+            alts = [j for j in alts if not (toks[j] in seen or seen.add(toks[j]))]
+            if not alts:
+                return nat
+            self.in_band += 1
+            if self.h is not None and self.h.synced_from[what[1]] < 0:
+                held = int(self.h.X[what[1], what[2]])
+                hit = [j for j in [nat] + alts if toks[j] == held]
+                if hit:
+                    return self._hinted(nat, hit[0])
+        elif kind == "leader":
+            self.in_band += 1
+            if self.h is not None:
+                src = [f for f in self.h.synced_from if f >= 0]
+                hit = [j for j in [nat] + alts if src and what[1 + j] == src[0]]
+                if hit:
+                    return self._hinted(nat, hit[0])
+        else:
+            self.in_band += 1
+        return self.choose([nat] + alts, ("max", kind, tuple(float(x) for x in v)))
+
+
+def enumerate_worlds(run, cap=MAX_WORLDS, accept=None):
+    """run(cmp) -> outcome.  Depth-first over the free choices as they come up; the first result is the literal
+    one.  Returns [(assignment, outcome)], stopping early at the first outcome accept() approves; raises if
+    more than `cap` runs would be needed."""
+    stack, out = [[]], []
+    while stack:
+        prefix = stack.pop()
+        cmp = run.make(prefix)
+        res = run(cmp)
+        picks = [p for p, _ in cmp.taken]
+        out.append((picks, res))
+        if accept is not None and accept(res):
+            break
+        if len(out) > cap:
+            raise AssertionError(f"more than {cap} guard-band combinations in one commit")
+        for j in range(len(prefix), len(cmp.taken)):
+            for alt in range(1, cmp.taken[j][1]):
+                stack.append(picks[:j] + [alt])
+    return out
+
+
+def oracle_state(o):
+    """Everything the commit decides, as a comparable value."""
+    br = tuple((b.start, b.end, bool(b.done), b.tokens_merged, b.synced_from, b.committed_threshold, b.committed_fallback,
+                tokens_decoded(o.X, b.k, o.L_p, o.mask_id)) for b in o.br)
+    return (o.X.astype(np.int64).tobytes(), br, bool(o.refresh_due), int(o.finished),
+            int(o.winner) if o.finished else -1, int(o.eos_pos) if o.finished else -1,
+            (o.nfe["init"], o.nfe["block"], o.nfe["refresh"]))
+
+
+def gpu_state(X, st, N):
+    br = tuple((g.start, g.end, bool(g.done), g.tokens_merged, g.synced_from, g.committed_threshold, g.committed_fallback,
+                g.tokens_decoded) for g in list(st.branch)[:N])
+    return (np.ascontiguousarray(X, dtype=np.int64).tobytes(), br, bool(st.refresh_due), int(st.finished), int(st.winner),
+            int(st.eos_pos), (st.nfe_init, st.nfe_block, st.nfe_refresh))
 
 
 class SideBySide:
-    def __init__(self, bb: BlockBatch, omodel: OracleModel, prompt, gen_len, blocks, decode):
+    def __init__(self, bb: BlockBatch, omodel: OracleModel, prompt, gen_len, blocks, decode, conf_tol=CONF_TOL):
+        """conf_tol: asserted bound on |confidence difference| per row (5e-3 suits every shape; where the
+        oracle runs in fp64 on a small model a tighter bound holds and narrows the pairwise band)."""
         self.bb = bb
+        self.conf_tol = conf_tol
         self.o = OracleRequest(omodel, prompt, gen_len, blocks, decode)
         self.rid = bb.request_open(prompt, gen_len, blocks)
         self.rep = Report()
-        self.diverged = False
 
     # -- forwards -----------------------------------------------------------------------------
     def _compare_forward(self, ref, view, sel=None):
@@ -51,7 +210,6 @@ class SideBySide:
         rep = self.rep
         n_mine = view.m_lm if sel is None else len(sel)
         assert n_mine == len(ref.pos), (n_mine, len(ref.pos))
-        self._argmax_fragile = False
         if n_mine == 0:
             return
         take = (lambda a: a) if sel is None else (lambda a: a[sel])
@@ -61,16 +219,24 @@ class SideBySide:
         rep.max_logit_err = max(rep.max_logit_err, float(err))
         rep.rows += n_mine
         assert err <= LOGIT_TOL, f"logits differ by {err}"
-        srt = np.sort(ref.logits[:, keep], axis=1)
-        margin = srt[:, -1] - srt[:, -2]
+        srt = np.partition(ref.logits[:, keep], -2, axis=1)[:, -2:]
+        margin = srt[:, 1] - srt[:, 0]
         clear = margin > GUARD
         rep.argmax_in_band += int((~clear).sum())
         am = take(view.argmax())
         assert np.array_equal(am[clear], ref.pred[clear]), "argmax differs at a clear-margin row"
-        cerr = np.abs(take(view.conf()) - ref.conf).max()
+        for j in np.nonzero(~clear)[0]:         # in the band the token must still be one of the near-top ones
+            assert ref.logits[j, am[j]] >= ref.logits[j, keep].max() - GUARD, "argmax outside the guard band"
+        gconf = take(view.conf())
+        self._obs_conf = {(int(k), int(i)): gconf[j] for j, (k, i) in enumerate(zip(ref.branch, ref.pos))}
+        self._obs_pred = {(int(k), int(i)): int(am[j]) for j, (k, i) in enumerate(zip(ref.branch, ref.pos))}
+        cerr = np.abs(gconf - ref.conf).max()
         rep.max_conf_err = max(rep.max_conf_err, float(cerr))
-        assert cerr <= 2e-2, f"confidence differs by {cerr}"
-        self._argmax_fragile = bool((~clear).any())
+        assert cerr <= self.conf_tol, f"confidence differs by {cerr}"
+        lse = take(view.lse())
+        ref_lse = np.log(np.exp(ref.logits[:, keep].astype(np.float64) - ref.logits[:, keep].max(axis=1, keepdims=True)).sum(axis=1)) \
+            + ref.logits[:, keep].max(axis=1)
+        assert np.abs(lse - ref_lse).max() <= LOGIT_TOL, "log-sum-exp differs"
 
     def init(self):
         full = self.o.init_forward()
@@ -78,7 +244,9 @@ class SideBySide:
         view = self.bb.latest_view()
         assert view.m_q == self.o.L
         self._compare_forward(full, view)
-        self._pending_ref = self.o.pending
+        # the common row's results stand for every branch (the initial cache and map are shared)
+        for d in (self._obs_conf, self._obs_pred):
+            d.update({(k, i): v for (_, i), v in list(d.items()) for k in range(1, self.o.N)})
 
     def step(self):
         self.oracle_step()
@@ -109,98 +277,78 @@ class SideBySide:
         self.oracle_commit()
         return self.check_commit(self.bb.merge_commit([self.rid])[0])
 
+    def _snapshot(self):
+        o = self.o
+        return (o.X.copy(), copy.deepcopy(o.br), o.pending, o.refresh_due, o.finished, o.winner, o.eos_pos)
+
+    def _restore(self, s):
+        o = self.o
+        o.X[:] = s[0]
+        o.br = copy.deepcopy(s[1])
+        o.pending, o.refresh_due, o.finished, o.winner, o.eos_pos = s[2], s[3], s[4], s[5], s[6]
+
     def oracle_commit(self):
-        o, rep, ref = self.o, self.rep, self._pending_ref
-        p = o.p
-        fragile = getattr(self, "_argmax_fragile", False)
-        # Eq. 1 guard bands on the rows about to be decoded
-        for br in o.br:
-            sel = ref.branch == br.k
-            if br.done or not sel.any():
-                continue
-            c = np.sort(ref.conf[sel])
-            if np.any(np.abs(ref.conf[sel] - p.tau_dec) <= GUARD):
-                fragile = True
-            if c[-1] < p.tau_dec + GUARD and len(c) > 1 and c[-1] - c[-2] <= GUARD:
-                fragile = True
-        decoded_now = o.decoded_branches()
-        commits = o.decode_all()
-        if o.eos_finish(decoded_now):
-            rep.commits += len(commits)
-            self._last = (fragile, commits, [], [])
-            return
-        o.advance_all()
-        # leader guard band
-        td = [tokens_decoded(o.X, k, o.L_p, o.mask_id) for k in range(o.N)]
-        mc = [b.mean_conf for b in o.br]
-        if p.leader_rule == 1:
-            s = sorted(mc)
-            if len(s) > 1 and s[-1] - s[-2] <= GUARD:
-                fragile = True
-        else:
-            top = [k for k in range(o.N) if td[k] == max(td)]
-            if len(top) > 1:
-                s = sorted(mc[k] for k in top)
-                if 0 < s[-1] - s[-2] <= GUARD:
-                    fragile = True
-        seen = {}
-
-        def prob(d, i, v):
-            pr = o.P[d, i - o.L_p, v]
-            nonlocal fragile
-            if abs(pr - p.tau_merge) <= GUARD:
-                fragile = True
-            for (v2, p2) in seen.setdefault((d, i), []):
-                if v2 != v and abs(p2 - pr) <= GUARD:
-                    fragile = True
-            seen[(d, i)].append((v, pr))
-            return pr
-
-        merges, syncs = o.merge_sync_all(prob)
-        o.end_of_commit()
-        rep.commits += len(commits); rep.merges += len(merges); rep.syncs += len(syncs)
-        self._last = (fragile, commits, merges, syncs)
+        """Fix the oracle's inputs of the commit (call before the library's bb_merge_commit of the same step):
+        rows whose argmax is within the guard band take the token the library reported, which the forward
+        comparison has checked to be one of the near-top ones."""
+        ref = self.o.pending
+        self._flips = 0
+        if ref is not None and len(ref.pos):
+            obs_pred = getattr(self, "_obs_pred", {})
+            top = ref.logits.max(axis=1)
+            pred = ref.pred.copy()
+            for j in np.nonzero((ref.logits >= (top - GUARD)[:, None]).sum(axis=1) > 1)[0]:
+                pred[j] = obs_pred.get((int(ref.branch[j]), int(ref.pos[j])), pred[j])
+            self._flips = int((pred != ref.pred).sum())
+            ref = ForwardResult(ref.branch, ref.pos, ref.logits, ref.conf, pred, ref.window_rows)
+        self._ref = ref
+        self._snap = self._snapshot()
 
     def check_commit(self, st):
-        o, rep = self.o, self.rep
-        fragile, commits, merges, syncs = self._last
+        """The library's complete state after its commit must equal the oracle's under some admissible choice of the
+        in-band decisions; the oracle continues from that outcome."""
+        o, rep, p = self.o, self.rep, self.o.p
         X = self.bb.get_tokens(self.rid)
-        same = np.array_equal(X, o.X)
+        got = gpu_state(X, st, o.N)
+        hints = SimpleNamespace(conf=getattr(self, "_obs_conf", {}), X=np.asarray(X), mask_id=o.mask_id,
+                                synced_from=[g.synced_from for g in list(st.branch)[:o.N]])
+        record = {}
+
+        def run(cmp):
+            self._restore(self._snap)
+            o.pending = self._ref
+            record["copies"] = []
+            info = o.commit_merge(cmp=cmp, copy_row=lambda a, b: record["copies"].append((a, b)))
+            return oracle_state(o), info, o.X.copy(), (cmp.decisions, cmp.in_band, cmp.flipped), list(record["copies"])
+
+        run.make = lambda prefix: GuardedComparisons(prefix, p.tau_dec, p.tau_merge, 2 * self.conf_tol, hints)
+        worlds = enumerate_worlds(run, accept=lambda res: res[0] == got)
+        rep.commit_steps += 1
+        rep.max_worlds = max(rep.max_worlds, len(worlds))
+        state, info, Xo, (n_dec, n_band, n_flip), copies = worlds[-1][1]
+        if state != got:
+            nat = worlds[0][1]
+            rows = [(k, np.nonzero(np.asarray(X[k]) != nat[2][k])[0].tolist()) for k in range(o.N)]
+            raise AssertionError(
+                f"GPU state after the commit matches none of the {len(worlds)} admissible outcomes; against the first one: "
+                f"token diffs {rows}; gpu={got[1:]} oracle={nat[0][1:]}")
+        # the oracle is in the accepted outcome (the last run); cache rows and maps follow now
+        for a, b in copies:
+            o._copy_row(a, b)
+        n_band += self._flips
+        rep.decisions += n_dec; rep.in_band += n_band; rep.flipped += n_flip + self._flips
+        rep.exact_steps += n_band == 0
+        rep.asserted_steps += n_dec > n_band or n_dec == 0
         for k, b in enumerate(o.br):
-            g = st.branch[k]
-            same &= (g.start, g.end, bool(g.done)) == (b.start, b.end, b.done)
-            same &= g.tokens_merged == b.tokens_merged and g.synced_from == b.synced_from
-            same &= g.committed_threshold == b.committed_threshold and g.committed_fallback == b.committed_fallback
-            same &= g.tokens_decoded == tokens_decoded(o.X, k, o.L_p, o.mask_id)
-        same &= bool(st.refresh_due) == bool(o.refresh_due)
-        same &= (st.finished, st.winner, st.eos_pos) == (o.finished, o.winner if o.finished else -1, o.eos_pos if o.finished else -1)
-        same &= (st.nfe_init, st.nfe_block, st.nfe_refresh) == (o.nfe["init"], o.nfe["block"], o.nfe["refresh"])
-        if fragile:
-            rep.fragile_steps += 1
-            if not same:
-                rep.fragile_mismatch += 1
-                gpu_syncs = {(k, st.branch[k].synced_from) for k in range(o.N) if st.branch[k].synced_from >= 0}
-                if gpu_syncs != set(syncs):
-                    self.diverged = True       # cache rows no longer comparable
-        else:
-            if not same:
-                rows = [(k, np.nonzero(X[k] != o.X[k])[0].tolist()) for k in range(o.N)]
-                raise AssertionError(f"state differs after a non-fragile commit: token diffs {rows}; "
-                                     f"gpu={[(g.start, g.end, g.done, g.tokens_merged, g.synced_from) for g in list(st.branch)[:o.N]]} "
-                                     f"oracle={[(b.start, b.end, b.done, b.tokens_merged, b.synced_from) for b in o.br]}")
-        # teacher forcing: the GPU continues from the oracle's state
-        if not same:
-            self.bb.set_state(self.rid, o.X, o.br)
-            for k, b in enumerate(o.br):       # counters on the GPU side may now lag; keep the oracle's in step
-                g = st.branch[k]
-                b.tokens_merged, b.committed_threshold, b.committed_fallback = g.tokens_merged, g.committed_threshold, g.committed_fallback
-        return {"commits": commits, "merges": merges, "syncs": syncs}
+            assert abs(st.branch[k].mean_conf - b.mean_conf) <= self.conf_tol, "mean confidence differs"
+        rep.commits += len(info["commits"]); rep.merges += len(info["merges"]); rep.syncs += len(info["syncs"])
+        return info
 
     def run(self, max_steps=10 ** 9, check_kv=None):
         self.init()
         self.commit()
         n = 0
-        while not self.o.all_done() and n < max_steps and not self.diverged:
+        while not self.o.all_done() and n < max_steps:
             if self.o.refresh_due:
                 self.refresh()
                 if check_kv:

@@ -12,14 +12,16 @@ pytestmark = pytest.mark.gpu
 
 
 def run_case(model, decode, prompt_len, gen_len, blocks, seed=0, max_steps=10 ** 9, kv=True, dtype=np.float64,
-             weights_device="cpu"):
+             weights_device="cpu", conf_tol=5e-4):
+    """conf_tol: with the oracle in fp64 on these small models the confidences agree to a few 1e-5, so a
+    tenth of the general bound is asserted and the pairwise guard band shrinks with it."""
     print(f"parity case {model.name} blocks={blocks} L_p={prompt_len} G={gen_len} seed={seed}", flush=True)
     weights = dict(gen_weights(model, seed, device=weights_device))
     om = OracleModel(model, weights, dtype)
     prompt = gen_prompt(model, seed, 0, prompt_len)
     bb = make_bb(model, decode, weights, len(blocks), prompt_len + gen_len, gen_len, sum(min(b, gen_len) for b in blocks))
     try:
-        sbs = SideBySide(bb, om, prompt, gen_len, blocks, decode)
+        sbs = SideBySide(bb, om, prompt, gen_len, blocks, decode, conf_tol=conf_tol)
 
         def check_kv(s):
             for k in range(s.o.N):
@@ -33,7 +35,7 @@ def run_case(model, decode, prompt_len, gen_len, blocks, seed=0, max_steps=10 **
                 sbs.compare_kv(k, model.n_layers - 1)
         sbs.commit()
         n = 0
-        while not sbs.o.all_done() and n < max_steps and not sbs.diverged:
+        while not sbs.o.all_done() and n < max_steps:
             if sbs.o.refresh_due:
                 sbs.refresh()
                 if kv:
@@ -41,18 +43,32 @@ def run_case(model, decode, prompt_len, gen_len, blocks, seed=0, max_steps=10 **
             sbs.step()
             sbs.commit()
             n += 1
+        sbs.final = bb.get_stats(sbs.rid)
         print("parity:", model.name, blocks, sbs.rep, flush=True)
         return sbs
     finally:
         bb.close()
 
 
+def check_report(s, min_asserted=0.9):
+    """Every commit was compared in full (the harness raises at the first state that is no admissible outcome); here:
+    nearly every commit carries decisions outside all guard bands (those are asserted exactly), most decisions are
+    outside, and the library rarely takes an in-band decision the other way than the oracle's literal rule."""
+    r = s.rep
+    assert r.commit_steps > 0 and r.asserted_steps >= min_asserted * r.commit_steps, r
+    assert r.decisions >= 4 * r.in_band, r
+    assert r.flipped <= max(3, r.in_band // 4), r
+    st = s.final
+    assert (st.finished, st.winner if st.finished else -1) == (s.o.finished, s.o.winner if s.o.finished else -1)
+
+
 def test_tiny_full_trajectory():
     w = workload("tiny")
     s = run_case(w.model, w.decode, 64, 64, w.block_sizes)
-    assert s.o.all_done() and not s.diverged
+    assert s.o.all_done()
     assert s.rep.max_logit_err <= 3e-2
     assert s.rep.merges > 0
+    check_report(s)
 
 
 @pytest.mark.parametrize("seed,blocks,prompt_len,gen_len,decode", [
@@ -69,18 +85,150 @@ def test_tiny_variants(seed, blocks, prompt_len, gen_len, decode):
     w = workload("tiny")
     s = run_case(w.model, decode, prompt_len, gen_len, blocks, seed=seed, max_steps=40)
     assert s.rep.max_logit_err <= 3e-2
+    check_report(s)
 
 
 def test_tiny_gqa_with_bias():
     shape = ModelShape("tiny_gqa", 2, 256, 4, 2, 64, 688, 1024, qkv_bias=True, lm_std=0.5)
     s = run_case(shape, DecodeParams(0.9, 0.5, 4, 4, 0), 50, 64, (8, 16, 32), seed=7, max_steps=20)
     assert s.rep.max_logit_err <= 3e-2
+    check_report(s)
 
 
 def test_head_dim_128_small():
     shape = ModelShape("small128", 2, 512, 4, 2, 128, 1024, 2048, lm_std=0.35)
     s = run_case(shape, DecodeParams(0.9, 0.5, 4, 4, 0), 200, 64, (8, 16, 32), seed=8, max_steps=12)
     assert s.rep.max_logit_err <= 3e-2
+    check_report(s)
+
+
+def test_last_page_holds_one_key():
+    """L = 2 * 64 + 1: the third cache page of every row holds a single key."""
+    w = workload("tiny")
+    s = run_case(w.model, DecodeParams(0.9, 0.5, 4, 3, 0), 65, 64, (8, 16, 32), seed=9, max_steps=8)
+    assert s.o.L == 129 and s.rep.max_logit_err <= 3e-2
+    check_report(s)
+
+
+def test_long_row_with_empty_attention_splits():
+    """L = 64 * 64 + 1 = 4097 keys against at most 32 query rows per branch: the block-step attention cuts the 65
+    pages of a row into 16 splits of 5 pages, of which the last three are empty, the last page holds one key, and
+    inside a split some waves get no page."""
+    w = workload("tiny")
+    s = run_case(w.model, DecodeParams(0.9, 0.5, 8, 3, 0), 4033, 64, (8, 16, 32), seed=10, max_steps=4, kv=False)
+    assert s.o.L == 4097 and s.rep.max_logit_err <= 3e-2
+    check_report(s)
+
+
+def test_vocabulary_reduction_ties_take_the_lowest_token_id():
+    """A duplicated LM-head row makes two logits of every row exactly equal (same dot product, same order, on the
+    GPU).  The duplicate of the token that wins the rows is placed next to it in the same 16-byte load, in another
+    lane, in another wave's stride and in other segments of the reduction, below and above: the reported argmax
+    must always be the lower id, and the confidence 1 / (sum) with both counted."""
+    from oracle.blockbatch import OracleRequest
+    from paper_2605_29233_amd import BB_INIT
+    w = workload("tiny")
+    base = dict(gen_weights(w.model, 0))
+    prompt = gen_prompt(w.model, 0, 0, 64)
+    rq = OracleRequest(OracleModel(w.model, base, np.float64), prompt, 64, w.block_sizes, w.decode)
+    pred = rq.init_forward().pred                       # top-1 token of every generation row, plain weights
+    V, mask = w.model.vocab, w.model.mask_id
+    checked = 0
+    for off in (1, -1, 5, -70, 300, -400, 257, -513):
+        weights = dict(base)
+        lm = base["lm_head"].clone()
+        pairs = []
+        for t in dict.fromkeys(int(t) for t in pred):
+            u = t + off
+            if 0 <= u < V and u != mask and u not in set(pred.tolist()) and all(u not in p and t not in p for p in pairs):
+                lm[u] = lm[t]
+                pairs.append((t, u))
+        assert pairs
+        weights["lm_head"] = lm
+        bb = make_bb(w.model, w.decode, weights, 3, 128, 64, sum(w.block_sizes))
+        try:
+            rid = bb.request_open(prompt, 64, w.block_sizes)
+            bb.refresh([rid], BB_INIT)
+            v = bb.latest_view()
+            lg, am, conf = v.logits(), v.argmax(), v.conf()
+            for t, u in pairs:
+                assert np.array_equal(lg[:, t], lg[:, u]), "duplicate LM-head rows must give identical logits"
+                for j in np.nonzero(pred == t)[0]:
+                    assert am[j] == min(t, u), (off, j, t, u, am[j])
+                    row = lg[j].astype(np.float64).copy(); row[mask] = -np.inf
+                    assert abs(conf[j] - 1.0 / np.exp(row - row.max()).sum()) <= 1e-5
+                    checked += 1
+        finally:
+            bb.close()
+    assert checked >= 8 * 8
+
+
+def test_equal_rows_give_bit_identical_logits_wherever_they_are_placed():
+    """Three branches of one block size in each of two request slots with the same prompt: all six rows see the same
+    tokens, so every row of a position must carry the same logit bits, whichever packed row, m-tile or request
+    slot it occupies (no atomics, fixed summation orders), step after step."""
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 4))
+    prompt = gen_prompt(w.model, 4, 0, 50)
+    bb = make_bb(w.model, w.decode, weights, 3, 50 + 48, 48, 6 * 16, max_requests=2)
+    try:
+        from paper_2605_29233_amd import BB_INIT, BB_PERIODIC
+        ids = [bb.request_open(prompt, 48, (16, 16, 16)) for _ in range(2)]
+        for r in ids:
+            bb.refresh([r], BB_INIT)
+        st = bb.merge_commit(ids)
+        for step in range(6):
+            if st[0].refresh_due:
+                bb.refresh(ids, BB_PERIODIC)
+            v = bb.denoise_step(ids)
+            gbr, pos = v.rows()
+            lm = v.lm_rows()
+            lg, am, conf = v.logits(), v.argmax(), v.conf()
+            assert v.m_q == 6 * 16 and v.m_lm % 6 == 0 and v.m_lm > 0
+            n = v.m_lm // 6
+            for b in range(1, 6):
+                assert np.array_equal(pos[lm][b * n:(b + 1) * n], pos[lm][:n])
+                assert np.array_equal(lg[b * n:(b + 1) * n, :-1], lg[:n, :-1]), f"row group {b} differs in step {step}"
+                assert np.array_equal(am[b * n:(b + 1) * n], am[:n]) and np.array_equal(conf[b * n:(b + 1) * n], conf[:n])
+            st = bb.merge_commit(ids)
+            X0 = bb.get_tokens(ids[0])
+            assert np.array_equal(bb.get_tokens(ids[1]), X0) and np.array_equal(X0[1], X0[0]) and np.array_equal(X0[2], X0[0])
+            assert all(x.tokens_merged == 0 and x.synced_from == -1 for s_ in st for x in list(s_.branch)[:3])
+            if st[0].finished:
+                break
+    finally:
+        bb.close()
+
+
+def test_eos_ready_after_the_initial_commit_waits_for_the_loop():
+    """Alg. 1 has CheckEOS inside its while loop only.  With seed 0 the initial commit of the tiny workload fills
+    the first generation position of every branch; taking that token as the EOS id makes all three branches
+    EOS-ready before any block forward, and both sides must keep running until the first loop iteration ends
+    the request (the harness compares finished / winner / eos_pos after every commit)."""
+    import dataclasses
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 0))
+    om = OracleModel(w.model, weights, np.float64)
+    from oracle.blockbatch import OracleRequest
+    prompt = gen_prompt(w.model, 0, 0, 64)
+    probe = OracleRequest(om, prompt, 64, w.block_sizes, w.decode)
+    probe.init_forward(); probe.commit_merge()
+    eos = int(probe.X[0, 64])
+    assert eos != w.model.mask_id and all(probe.X[k, 64] == eos for k in range(3))
+    decode = dataclasses.replace(w.decode, eos_id=eos)
+    bb = make_bb(w.model, decode, weights, 3, 128, 64, sum(w.block_sizes))
+    try:
+        s = SideBySide(bb, om, prompt, 64, w.block_sizes, decode, conf_tol=5e-4)
+        s.init()
+        s.commit()
+        st = bb.get_stats(s.rid)
+        assert st.finished == 0 and s.o.finished == 0 and st.nfe_block == 0
+        s.step()
+        s.commit()
+        st = bb.get_stats(s.rid)
+        assert (st.finished, st.eos_pos, st.nfe_block) == (2, 64, 1) and s.o.finished == 2 and st.winner == s.o.winner
+    finally:
+        bb.close()
 
 
 # ---- CheckEOS / winner selection and the Alg. 1 driver ----------------------------------------------------
@@ -102,8 +250,9 @@ def test_tiny_eos_parity(seed, blocks, prompt_len, gen_len):
     eos = _eos_token_of_plain_run(w.model, w.decode, prompt_len, gen_len, blocks, seed, weights)
     decode = dataclasses.replace(w.decode, eos_id=eos)
     s = run_case(w.model, decode, prompt_len, gen_len, blocks, seed=seed)
-    assert s.o.finished in (1, 2) and not s.diverged
+    assert s.o.finished in (1, 2)
     assert s.rep.max_logit_err <= 3e-2
+    check_report(s)
     print("eos case finished =", s.o.finished, "winner", s.o.winner, "eos_pos", s.o.eos_pos, flush=True)
 
 
@@ -182,7 +331,7 @@ def test_tiny_eos_cycle_parity():
             s.commit()
             n += 1
         print("eos cycle: finished", s.o.finished, "after", n, "steps; winner", s.o.winner, "eos_pos", s.o.eos_pos, s.rep, flush=True)
-        assert s.o.finished == 2 and n >= 2 and not s.diverged
+        assert s.o.finished == 2 and n >= 2 and bb.get_stats(s.rid).finished == 2
         assert s.rep.max_logit_err <= 3e-2
     finally:
         bb.close()
@@ -206,7 +355,7 @@ def test_kv_diagnostics_match_oracle():
         for _ in range(3):
             s.step()
             s.commit()
-        assert not s.o.all_done() and not s.diverged
+        assert not s.o.all_done()
         Pref, Dref = dispersion(s.o)
         _, P, D = bb.kv_diagnostics(s.rid, want_error=False)
         scale = max(Pref.max(), 1e-30)

@@ -52,6 +52,8 @@ def single_request(name, steps, refresh_after=None):
             s.commit()
             print(f"[{name}] step {i} compared in {time.time() - t:.1f}s: {s.rep}", flush=True)
         assert s.rep.max_logit_err <= 3e-2
+        # every commit above was matched against the admissible outcomes (the harness raises otherwise)
+        assert s.rep.commit_steps == steps + 1 and s.rep.asserted_steps == s.rep.commit_steps and s.rep.decisions > 10 * s.rep.in_band, s.rep
         return s
     finally:
         bb.close()
@@ -111,5 +113,6 @@ def test_llada_16_requests_sampled():
             print(f"[llada_x16] step {i}: m_q={view.m_q} " + " | ".join(str(s.rep) for s in sampled.values()), flush=True)
         for s in sampled.values():
             assert s.rep.max_logit_err <= 3e-2
+            assert s.rep.commit_steps == 3 and s.rep.asserted_steps == 3, s.rep
     finally:
         bb.close()
