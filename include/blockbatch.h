@@ -227,6 +227,23 @@ int bb_profile_read(bb_ctx* ctx, bb_profile_entry* out_host, int max_entries, in
 int bb_debug_gemm(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, float* C_host,
                   int M, int N, int K, int split_k);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): C[M][N] = A[M][K] . W[N][K]^T through the same re-tiling,
+ * packing and MFMA kernels as the forward's projections, with every intermediate buffer (tiled weights, packed
+ * hi/lo activation panel, split-K partial tiles) in a file-scope device array of 18 MiB that each GPU the
+ * library runs on holds until the process ends.  No context is needed.
+ *   A_dev fp32 row-major, W_dev bf16 bits row-major (16-byte aligned), C_dev fp32 row-major: device memory owned
+ *   by the caller; hip_stream: a hipStream_t (NULL = default stream).  All work is enqueued on it; nothing is
+ *   allocated, freed, memset or synchronised, so the call may be captured into a graph.
+ *   Limits: 1 <= M <= 128; 32 <= N <= 4096, N % 32 == 0; 16 <= K <= 4096, K % 16 == 0; N * K64 <= 4 Mi with K64
+ *   = K rounded up to 64; split_k 0 (the library chooses, at most 4) .. 4.  Beyond them: BB_ENOMEM; malformed
+ *   arguments: BB_EINVAL; a HIP error: BB_EHIP (there is no context, hence no bb_last_error text).
+ *   The array is shared by every call on that GPU and keeps the last call's contents (the call clears what it
+ *   needs cleared): calls on different streams of one GPU that overlap in time race; serialise them.
+ *   Results equal bb_debug_gemm's for the same split_k bit for bit (same kernels, same summation order). */
+int bb_gemm_static(const float* A_dev, const uint16_t* W_dev, float* C_dev, int M, int N, int K, int split_k,
+                   void* hip_stream);
+
 /* Tuning knob: override the tile width (nt = 1: 128 columns, 2: 256; 0 = heuristic) and the
  * split-K factor (0 = heuristic) of one GEMM kind (0 LM head, 1 O/down, 2 gate/up, 3 QKV) for
  * panels of at most 128 rows.  Results are unchanged up to fp32 summation order. */

@@ -64,7 +64,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -109,8 +109,23 @@ def load_library():
         lib.bb_kv_diagnostics.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.bb_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         lib.bb_debug_copy16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
+        lib.bb_gemm_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         _LIB = lib
     return _LIB
+
+
+def gemm_static(A, W_bits, C_out, split_k=0, stream=None):
+    """bb_gemm_static on torch CUDA tensors: A fp32 [M][K], W_bits int16 (bf16 bit patterns) [N][K], C_out fp32
+    [M][N] (written in place).  Marshalling only; returns the library's return code."""
+    import torch
+    assert A.is_cuda and W_bits.is_cuda and C_out.is_cuda and A.is_contiguous() and W_bits.is_contiguous() and C_out.is_contiguous()
+    assert A.dtype == torch.float32 and C_out.dtype == torch.float32 and W_bits.element_size() == 2
+    M, K = A.shape
+    N = W_bits.shape[0]
+    assert W_bits.shape[1] == K and tuple(C_out.shape) == (M, N)
+    st = stream if stream is not None else torch.cuda.current_stream(A.device)
+    return load_library().bb_gemm_static(C.c_void_p(A.data_ptr()), C.c_void_p(W_bits.data_ptr()), C.c_void_p(C_out.data_ptr()),
+                                         M, N, K, int(split_k), C.c_void_p(st.cuda_stream))
 
 
 class StepView:
