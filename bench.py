@@ -4,14 +4,24 @@ A "step" is one pass of the whole hot path: bb_denoise_step (pack, batched block
 head, vocabulary reduction) + bb_merge_commit (Eq. 1 commit, merge, sync), plus the periodic
 full-sequence refresh whenever R block forwards have run.  `value` is steps/s of a free-running
 decode (refreshes included, inputs and weights resident in HBM; a request that finishes inside the
-timed region is opened again, so every counted step is a real block forward); the steady-state block forward,
-the refresh and the committed-token rate are reported beside it.  The roofline figure is for the
-weight-streaming MFMA GEMM launches of the block forward at a frozen, fully masked state, timed
-with HIP events on the library's stream; the CPU oracle is timed on the host for reference.
+timed region is opened again, so every counted step is a real block forward).  Beside it:
+
+  * the steady-state step (bb_denoise_step + bb_merge_commit at a frozen state with every window fully
+    masked, the worst case): median and mean over the timed iterations, each bracketed by events on the
+    library's stream; the block forward alone; the periodic refresh alone; the committed-token rate;
+  * `roofline`: the weight-streaming MFMA GEMM launches of the block forward against the HBM peak, from
+    per-launch HIP events on the library's stream (raw, and with the measured cost of the event packets
+    taken off), with the HBM traffic per launch that rocprofv3 counters gave for the same kernels;
+  * `roofline_kv`: the block forward's attention launches against the HBM peak (K,V streamed per step);
+  * `measured_peaks`: what a plain 16-byte-per-lane copy and a pure MFMA loop reach on this very GPU;
+  * `other_workloads`: steady step, refresh and both rooflines for the long-context and 16-request shapes;
+  * `cpu_baseline`: the CPU oracle timed on the host for reference.
 """
 import argparse
 import json
 import os
+import re
+import statistics
 import sys
 import time
 
@@ -22,11 +32,127 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-# HBM bytes per GEMM launch of a block forward from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), each scaled
-# by what the counter reads for a plain 16-byte-per-lane copy of known size (FETCH_SIZE x 2.000, WRITE_SIZE x
-# 1.000); the per-kernel table and the commands are in profiles/llada_hbm_traffic_pmc.md.  Counters cannot be
-# read from inside this process, so the figure is the stored one for the workload it was measured on.
-GEMM_TRAFFIC_BYTES_PER_LAUNCH = {"llada": 152.8e6}
+def stored_gemm_traffic(workload_name):
+    """HBM bytes per GEMM launch of a block forward from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each
+    scaled by what the counter reads for a plain copy of known size).  Counters cannot be read from inside this
+    process, so the figure is the one stored with the profile summary, which names the commit it was measured at:
+    a line `gemm_traffic_bytes_per_launch[<workload>] = <bytes> @ <commit>` in profiles/llada_hbm_traffic_pmc.md."""
+    try:
+        text = open(os.path.join(ROOT, "profiles", "llada_hbm_traffic_pmc.md")).read()
+    except OSError:
+        return None, None
+    m = re.search(r"gemm_traffic_bytes_per_launch\[%s\]\s*=\s*([0-9.eE+]+)\s*@\s*(\w+)" % re.escape(workload_name), text)
+    return (float(m.group(1)), m.group(2)) if m else (None, None)
+
+
+def make_context(w, torch):
+    from workload import gen_weights
+    from paper_2605_29233_amd import BlockBatch, Limits
+    m = w.model
+    L = max(w.prompt_lens) + w.gen_len
+    step_rows = w.n_requests * sum(min(b, w.gen_len) for b in w.block_sizes)
+    bb = BlockBatch(m, w.decode, Limits(w.n_requests, len(w.block_sizes), L, w.gen_len, step_rows))
+    bb.load_weights(gen_weights(m, w.seed, device="cuda:0"))
+    torch.cuda.empty_cache()
+    return bb, step_rows
+
+
+def open_all(bb, w):
+    from workload import gen_prompt
+    from paper_2605_29233_amd import BB_INIT
+    ids = [bb.request_open(gen_prompt(w.model, w.seed, r, lp), w.gen_len, w.block_sizes) for r, lp in enumerate(w.prompt_lens)]
+    for r in ids:
+        bb.refresh([r], BB_INIT)
+    return ids
+
+
+def steady_state(bb, w, ids, steps, warmup, profile_steps, torch):
+    """Frozen state right after the initial forward (every window fully masked).  Returns the timings of the
+    block forward alone, of denoise + commit per step, the per-class kernel times and the two rooflines."""
+    from paper_2605_29233_amd import BB_PERIODIC
+    m = w.model
+    frozen = [(bb.get_tokens(r).copy(), list(bb.get_stats(r).branch)[:len(w.block_sizes)]) for r in ids]
+    for _ in range(warmup):
+        bb.denoise_step(ids, want_view=False)
+    bb.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        bb.denoise_step(ids, want_view=False)
+    bb.synchronize()
+    fwd_ms = (time.perf_counter() - t0) * 1e3 / steps
+
+    # denoise + commit, one pair of events per step on the library's stream (= torch's current stream here);
+    # the state is put back between steps, outside the events
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        bb.denoise_step(ids, want_view=False)
+        bb.merge_commit(ids, want_stats=False)
+        b.record()
+        bb.synchronize()
+        for r, (X, br) in zip(ids, frozen):
+            bb.set_state(r, X, br)
+    step_ms = [a.elapsed_time(b) for a, b in ev]
+
+    # per-kernel-class timing of the frozen block forward (HIP events around every launch)
+    bb.profile_enable(True)
+    for _ in range(profile_steps):
+        bb.denoise_step(ids, want_view=False)
+    prof = bb.profile_read()
+    bb.profile_enable(False)
+    g = prof["gemm_skinny"] if prof["gemm_skinny"]["launches"] else prof["gemm_wide"]
+    # the event packet after every launch lengthens the profiled forward; its cost per launch is what the
+    # profiled forward takes beyond the unprofiled one, spread over the launches
+    all_launches = sum(v["launches"] for v in prof.values())
+    all_ms = sum(v["total_ms"] for v in prof.values())
+    ev_ms = max(0.0, (all_ms - fwd_ms * profile_steps) / max(all_launches, 1))
+    n = max(g["launches"], 1)
+    raw_ms, corr_ms = g["total_ms"], max(g["total_ms"] - ev_ms * g["launches"], 1e-9)
+    per_step = {k: v["total_ms"] / profile_steps for k, v in prof.items()}
+    per_step_corr = {k: (v["total_ms"] - ev_ms * v["launches"]) / profile_steps for k, v in prof.items()}
+    hbm_bound = g is prof["gemm_skinny"]
+    traffic, commit = stored_gemm_traffic(w.name)
+    gbs = g["bytes"] / 1e9 / (raw_ms / 1e3)
+    tfl = g["flops"] / 1e12 / (raw_ms / 1e3)
+    roof = {"bound": "hbm" if hbm_bound else "mfma",
+            "kernel": "gemm_kernel (MFMA GEMM launches of the block forward: %s)" % ("weight streaming" if hbm_bound else "many rows"),
+            "achieved": gbs if hbm_bound else tfl, "peak": HBM_PEAK_GBS if hbm_bound else MFMA_BF16_PEAK_TFLOPS,
+            "unit": "GB/s" if hbm_bound else "TFLOP/s",
+            "frac": gbs / HBM_PEAK_GBS if hbm_bound else tfl / MFMA_BF16_PEAK_TFLOPS,
+            "traffic": traffic, "traffic_unit": "bytes/launch", "traffic_measured_at_commit": commit,
+            "algorithmic_bytes_per_launch": g["bytes"] / n, "algorithmic_flops_per_launch": g["flops"] / n,
+            "avg_launch_ms": raw_ms / n, "launches": g["launches"],
+            "avg_launch_ms_event_corrected": corr_ms / n, "event_packet_ms_per_launch": ev_ms,
+            "frac_event_corrected": (g["bytes"] / 1e9 / (corr_ms / 1e3) / HBM_PEAK_GBS) if hbm_bound
+            else (g["flops"] / 1e12 / (corr_ms / 1e3) / MFMA_BF16_PEAK_TFLOPS),
+            "hbm_gbs": gbs, "mfma_tflops_nominal": tfl, "mfma_tflops_two_pass": 2 * tfl,
+            "note": "nominal flops 2*M*N*K; the hi+lo activation terms double the MFMA work (two_pass)"}
+    # attention of the block forward: K and V of every active branch row are streamed once per layer.  Algorithmic
+    # bytes = 2 B per cached element (n_kv_heads * head_dim keys + as many values per token); the cache holds two
+    # fp16 terms per element, so the kernel actually streams twice that.
+    at = prof["attention"]
+    rows_tokens = sum(lp + w.gen_len for lp in w.prompt_lens) * len(w.block_sizes)
+    kv_bytes = 2.0 * m.n_kv_heads * m.head_dim * 2 * rows_tokens * m.n_layers
+    at_ms = at["total_ms"] / profile_steps
+    kv = {"bound": "hbm", "kernel": "attention_kernel (block forward, paged K,V of every branch row)",
+          "achieved": kv_bytes / 1e9 / (at_ms / 1e3), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+          "frac": kv_bytes / 1e9 / (at_ms / 1e3) / HBM_PEAK_GBS,
+          "algorithmic_bytes_per_forward": kv_bytes, "streamed_bytes_per_forward": 2 * kv_bytes,
+          "frac_of_streamed_bytes": 2 * kv_bytes / 1e9 / (at_ms / 1e3) / HBM_PEAK_GBS,
+          "attention_ms_per_forward": at_ms, "launches_per_forward": at["launches"] / profile_steps}
+
+    # refresh alone
+    bb.merge_commit(ids, want_stats=False)
+    bb.refresh(ids, BB_PERIODIC)
+    bb.synchronize()
+    t0 = time.perf_counter()
+    bb.refresh(ids, BB_PERIODIC)
+    bb.synchronize()
+    refresh_ms = (time.perf_counter() - t0) * 1e3
+    return {"block_forward_ms_steady": fwd_ms, "step_ms_steady_median": statistics.median(step_ms),
+            "step_ms_steady_mean": statistics.fmean(step_ms), "steps_per_s_steady_median": 1e3 / statistics.median(step_ms),
+            "refresh_ms": refresh_ms, "kernel_ms_per_block_forward": per_step,
+            "kernel_ms_per_block_forward_event_corrected": per_step_corr, "roofline": roof, "roofline_kv": kv}
 
 
 def main():
@@ -39,6 +165,8 @@ def main():
     ap.add_argument("--refresh-interval", type=int, default=0, help="override the workload's R (App. E.3 sweeps)")
     ap.add_argument("--tau-sync", type=int, default=-1, help="override the workload's tau_sync (App. E.3 sweeps)")
     ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--other-workloads", default="llada_long,llada_x16",
+                    help="comma-separated workloads whose steady step, refresh and rooflines are reported beside the main one ('' = none)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -49,7 +177,7 @@ def main():
     import numpy as np
     import torch
     from workload import workload, gen_weights, gen_prompt
-    from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT, BB_PERIODIC
+    from paper_2605_29233_amd import BB_INIT, BB_PERIODIC
 
     w = workload(args.workload)
     if args.refresh_interval > 0 or args.tau_sync >= 0:
@@ -59,62 +187,34 @@ def main():
                                 tau_sync=args.tau_sync if args.tau_sync >= 0 else d.tau_sync)
         w = dataclasses.replace(w, decode=d)
     m = w.model
-    L = max(w.prompt_lens) + w.gen_len
-    step_rows = w.n_requests * sum(min(b, w.gen_len) for b in w.block_sizes)
     torch.cuda.set_device(0)
-    bb = BlockBatch(m, w.decode, Limits(w.n_requests, len(w.block_sizes), L, w.gen_len, step_rows))
-    bb.load_weights(gen_weights(m, w.seed, device="cuda:0"))
-    torch.cuda.empty_cache()
-
-    def open_all():
-        ids = [bb.request_open(gen_prompt(m, w.seed, r, lp), w.gen_len, w.block_sizes) for r, lp in enumerate(w.prompt_lens)]
-        for r in ids:
-            bb.refresh([r], BB_INIT)
-        return ids
-
-    def decoded(stats):
-        return sum(st.branch[k].tokens_decoded for st in stats for k in range(st.n_branches))
-
+    bb, step_rows = make_context(w, torch)
     R = w.decode.refresh_interval
 
-    # ---- 1. steady state at a frozen, fully masked state: block forward only --------------------
-    ids = open_all()
-    for _ in range(args.warmup):
-        bb.denoise_step(ids, want_view=False)
-    bb.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        bb.denoise_step(ids, want_view=False)
-    bb.synchronize()
-    fwd_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # ---- 1.-3. steady state, per-kernel-class timing, refresh alone -----------------------------------
+    ids = open_all(bb, w)
+    steady = steady_state(bb, w, ids, args.steps, args.warmup, args.profile_steps, torch)
 
-    # ---- 2. per-kernel-class timing of the same frozen block forward (HIP events) ---------------
-    bb.profile_enable(True)
-    for _ in range(args.profile_steps):
-        bb.denoise_step(ids, want_view=False)
-    prof = bb.profile_read()
-    bb.profile_enable(False)
-    g = prof["gemm_skinny"] if prof["gemm_skinny"]["launches"] else prof["gemm_wide"]
-    # The event packet after every launch lengthens the profiled forward; its cost per launch is what the profiled
-    # forward takes beyond the unprofiled one (measured just above), spread over the launches, and is taken off.
-    all_launches = sum(v["launches"] for v in prof.values())
-    all_ms = sum(v["total_ms"] for v in prof.values())
-    ev_ms = max(0.0, (all_ms - fwd_ms * args.profile_steps) / max(all_launches, 1))
-    gemm_raw_ms = g["total_ms"] / max(g["launches"], 1)
-    gemm_total_ms = max(g["total_ms"] - ev_ms * g["launches"], 1e-9)
-    gemm_ms = gemm_total_ms / max(g["launches"], 1)
-    gemm_gbs = g["bytes"] / 1e9 / (gemm_total_ms / 1e3)
-    gemm_tflops = g["flops"] / 1e12 / (gemm_total_ms / 1e3)
-    per_step = {k: (v["total_ms"] - ev_ms * v["launches"]) / args.profile_steps for k, v in prof.items()}
-
-    # ---- 3. refresh alone --------------------------------------------------------------------------
-    bb.merge_commit(ids, want_stats=False)
-    bb.refresh(ids, BB_PERIODIC)
+    # ---- measured peaks on this GPU: a plain copy with the library's access width, a pure MFMA loop ----
+    src = torch.ones(1 << 28, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    bb.debug_copy16(src, dst)
     bb.synchronize()
-    t0 = time.perf_counter()
-    bb.refresh(ids, BB_PERIODIC)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(8):
+        bb.debug_copy16(src, dst)
+    e1.record()
     bb.synchronize()
-    refresh_ms = (time.perf_counter() - t0) * 1e3
+    copy_gbs = 8 * 2 * src.numel() / 1e9 / (e0.elapsed_time(e1) / 1e3)
+    if args.copy_calibration:
+        assert bool((dst == 1).all())
+    del src, dst
+    mfma_tflops = bb.debug_mfma_rate()
+    peaks = {"copy_read_plus_write_GBps": copy_gbs, "mfma_bf16_32x32x16_TFLOPs": mfma_tflops,
+             "copy_frac_of_hbm_peak": copy_gbs / HBM_PEAK_GBS, "mfma_frac_of_nominal_peak": mfma_tflops / MFMA_BF16_PEAK_TFLOPS}
+    steady["roofline"]["frac_of_measured_copy"] = steady["roofline"]["hbm_gbs"] / copy_gbs
+    steady["roofline"]["two_pass_mfma_frac_of_measured_rate"] = steady["roofline"]["mfma_tflops_two_pass"] / mfma_tflops
 
     # ---- 4. free-running decode: the timed region ---------------------------------------------------
     # Every timed step is a real block forward: the per-request flags are read back after each commit (one
@@ -182,27 +282,29 @@ def main():
                    "refresh_interval": R, "tau_dec": w.decode.tau_dec, "tau_sync": w.decode.tau_sync},
         "committed_tokens_per_s": committed / dt, "committed_tokens": committed, "refreshes_in_timed_region": int(n_refresh),
         "requests_completed_in_timed_region": tally["completed"], "initial_forwards_in_timed_region": tally["init"],
-        "block_forward_ms_steady": fwd_ms, "block_forward_steps_per_s_steady": 1e3 / fwd_ms, "refresh_ms": refresh_ms,
-        "kernel_ms_per_block_forward": per_step,
-        "roofline": {"bound": "hbm", "kernel": "gemm_kernel (weight-streaming MFMA GEMM, block forward)",
-                     "achieved": gemm_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gemm_gbs / HBM_PEAK_GBS,
-                     "traffic": GEMM_TRAFFIC_BYTES_PER_LAUNCH.get(w.name), "traffic_unit": "bytes/launch",
-                     "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1),
-                     "avg_launch_ms": gemm_ms, "avg_launch_ms_with_event_packets": gemm_raw_ms,
-                     "event_packet_ms_per_launch": ev_ms, "launches": g["launches"],
-                     "mfma_tflops": gemm_tflops, "mfma_frac_of_bf16_peak": gemm_tflops / MFMA_BF16_PEAK_TFLOPS},
+        "measured_peaks": peaks,
     }
-    if args.copy_calibration:
-        # one plain copy of known size (256 MiB in, 256 MiB out, 16 bytes per lane like the library's kernels)
-        src = torch.ones(1 << 28, dtype=torch.uint8, device="cuda:0")
-        dst = torch.empty_like(src)
-        bb.debug_copy16(src, dst)
-        bb.synchronize()
-        assert bool((dst == 1).all())
-        del src, dst
+    out.update(steady)
     bb.close()
     del bb
     torch.cuda.empty_cache()
+
+    # ---- other workloads: steady step, refresh, rooflines (no free-running loop) -----------------------
+    others = {}
+    for name in [n for n in args.other_workloads.split(",") if n and n != w.name]:
+        wo = workload(name)
+        bo, rows_o = make_context(wo, torch)
+        ido = open_all(bo, wo)
+        so = steady_state(bo, wo, ido, max(4, args.steps // 4), 2, 2, torch)
+        so["config"] = {"workload": wo.name, "requests": wo.n_requests, "packed_rows": rows_o, "gen_len": wo.gen_len,
+                        "prompt_len": [min(wo.prompt_lens), max(wo.prompt_lens)], "block_sizes": list(wo.block_sizes)}
+        so["roofline"]["two_pass_mfma_frac_of_measured_rate"] = so["roofline"]["mfma_tflops_two_pass"] / mfma_tflops
+        others[name] = so
+        bo.close()
+        del bo
+        torch.cuda.empty_cache()
+    if others:
+        out["other_workloads"] = others
 
     # ---- 5. the CPU oracle on the host cores (reported baseline, bounded sample) ----------------------
     if not args.no_cpu_baseline:

@@ -152,7 +152,9 @@ int bb_request_open(bb_ctx* ctx, const int32_t* prompt_host, int L_p, int G,
 int bb_request_close(bb_ctx* ctx, int req_id);
 
 /* Full-sequence forward(s).  BB_INIT: once per request, before anything else.  BB_PERIODIC:
- * recompute the cache row of every unfinished branch from its current tokens. */
+ * recompute the cache row of every unfinished branch from its current tokens.  The listed requests are
+ * packed into one forward as long as their rows fit the activation buffers (which hold max_branches *
+ * max_seq_len rows), else into several. */
 int bb_refresh(bb_ctx* ctx, const int* req_ids_host, int n, int mode);
 
 /* One batched block forward over the current windows of all unfinished branches of the
@@ -167,8 +169,9 @@ int bb_merge_commit(bb_ctx* ctx, const int* req_ids_host, int n, bb_request_stat
 /* Alg. 1 from start to end for requests that were opened and not yet initialised: the initial full
  * forward of each, then { block forward, commit / CheckEOS / merge / sync, refresh when due } over the
  * requests still running, until every one has finished (all branches done, or an EOS-ready branch
- * selected) or max_block_forwards batched forwards have run.  Reads each request's flags back after
- * every commit (one small copy per step).  stats_out_host: n entries (may be NULL).  The output of
+ * selected) or max_block_forwards batched forwards have run.  The loop reads one flags word per listed
+ * request back (a single small copy) only when a refresh may fall due or the forward limit is reached:
+ * in between, up to R forwards are enqueued back to back.  stats_out_host: n entries (may be NULL).  The output of
  * request i is row stats[i].winner of bb_get_tokens, up to stats[i].eos_pos if that is >= 0.
  * Returns BB_OK also when the forward limit stopped it (finished == 0 then). */
 int bb_generate(bb_ctx* ctx, const int* req_ids_host, int n, int max_block_forwards, bb_request_stats* stats_out_host);
@@ -254,6 +257,12 @@ int bb_debug_set_gemm_plan(bb_ctx* ctx, int kind, int nt, int split_k);
  * width of the library's kernels.  A known-size reference for scaling hardware traffic counters, whose
  * reading per byte depends on the request size.  Asynchronous; BB_EINVAL on misaligned arguments. */
 int bb_debug_copy16(bb_ctx* ctx, const void* src_dev, void* dst_dev, size_t bytes);
+
+/* Measurement aid: the rate at which this chip issues dense 32x32x16 bf16 MFMAs when it does nothing else (1024
+ * workgroups of four waves, eight independent accumulator tiles per wave), in TFLOP/s, timed with HIP events on
+ * the context's stream after a warm-up launch of the same length (about 20 ms each, so that the clocks settle under the load).  The measured denominator quoted beside the nominal 2.5 PFLOP/s.
+ * Uses the activation region of the workspace as its output; synchronises the stream. */
+int bb_debug_mfma_rate(bb_ctx* ctx, double* tflops_out_host);
 
 #ifdef __cplusplus
 }

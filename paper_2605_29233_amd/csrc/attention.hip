@@ -87,17 +87,20 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* 
     __shared__ float sO[4][32][HD + 1];
     __shared__ float sM[4][32], sL[4][32];
 
+    // Grid = (kv head, query tile [x split], segment).  The kv head is the fastest index on purpose: workgroups go
+    // to the eight XCDs round robin by linear id, so with a multiple of eight kv heads all query tiles and page
+    // splits of one (branch, kv head) land on the same XCD and its L2 fetches that row's pages from HBM once.
     const int gbr = seg_base + blockIdx.z;
     const int seg_rows = D.seg_rows[gbr];
     if (seg_rows == 0) return;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, g = lane >> 5, c = lane & 31;
     const int group = D.hq / D.hkv, nflat = seg_rows * group;
-    // block steps may also split a row's pages over n_splits workgroups (blockIdx.x = tile * n_splits + split)
-    const int split = SPLITQ ? 0 : blockIdx.x % n_splits, qtile = SPLITQ ? blockIdx.x : blockIdx.x / n_splits;
+    // block steps may also split a row's pages over n_splits workgroups (blockIdx.y = tile * n_splits + split)
+    const int split = SPLITQ ? 0 : blockIdx.y % n_splits, qtile = SPLITQ ? blockIdx.y : blockIdx.y / n_splits;
     const int wg_base = qtile * (SPLITQ ? 128 : 32);
     if (wg_base >= nflat) return;
     const int tile_base = SPLITQ ? wg_base + 32 * wave : wg_base;     // this wave's 32 query rows
-    const int kvh = blockIdx.y, seg_off = D.seg_off[gbr];
+    const int kvh = blockIdx.x, seg_off = D.seg_off[gbr];
     const int L = D.hdr[gbr / D.max_br].L, n_pages = (L + BB_PAGE - 1) / BB_PAGE;
 
     // Q fragments (B operand).  The contraction index may be enumerated in any order as long as K uses the
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* 
     constexpr int ROWS = SPLITQ ? 128 : 32;
     if (!SPLITQ && n_splits > 1) {
         // unnormalised partial result of this split: max[32], sum[32], O[32][HD]; attention_combine_kernel finishes
-        float* dst = part + ((((size_t)blockIdx.z * gridDim.y + blockIdx.y) * (gridDim.x / n_splits) + qtile) * n_splits + split) * (64 + 32 * HD);
+        float* dst = part + ((((size_t)blockIdx.z * gridDim.x + blockIdx.x) * (gridDim.y / n_splits) + qtile) * n_splits + split) * (64 + 32 * HD);
         for (int item = threadIdx.x; item < 32 * (HD / 4); item += 256) {
             const int q = item / (HD / 4), d4 = item % (HD / 4);
             float M = sM[0][q];
@@ -264,10 +267,10 @@ __global__ __launch_bounds__(256) void attention_combine_kernel(Dev D, const flo
     const int gbr = seg_base + blockIdx.z;
     const int seg_rows = D.seg_rows[gbr];
     if (seg_rows == 0) return;
-    const int group = D.hq / D.hkv, nflat = seg_rows * group, wg_base = blockIdx.x * 32;
+    const int group = D.hq / D.hkv, nflat = seg_rows * group, wg_base = blockIdx.y * 32;
     if (wg_base >= nflat) return;
-    const int kvh = blockIdx.y, seg_off = D.seg_off[gbr];
-    const float* src = part + (((size_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * n_splits * (64 + 32 * HD);
+    const int kvh = blockIdx.x, seg_off = D.seg_off[gbr];
+    const float* src = part + (((size_t)blockIdx.z * gridDim.x + blockIdx.x) * gridDim.y + blockIdx.y) * n_splits * (64 + 32 * HD);
     for (int item = threadIdx.x; item < 32 * (HD / 8); item += 256) {
         const int q = item / (HD / 8), d8 = item % (HD / 8);
         const int f = wg_base + q;
@@ -304,7 +307,7 @@ void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int 
                       int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, hipStream_t s) {
     const int group = D.hq / D.hkv, nflat = max_seg_rows * group;
     if (nflat >= 512) {     // many query rows per segment: waves take different query tiles
-        dim3 grid((nflat + 127) / 128, D.hkv, n_segs);
+        dim3 grid(D.hkv, (nflat + 127) / 128, n_segs);
         if (D.hd == 128) attention_kernel<128, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr);
         else attention_kernel<64, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr);
         return;
@@ -315,7 +318,7 @@ void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int 
     int n_splits = std::min(std::min(256 / tiles, (max_pages + 3) / 4), 16);
     while (n_splits > 1 && (size_t)tiles * n_splits * (64 + 32 * D.hd) > part_elems) --n_splits;
     if (n_splits < 1) n_splits = 1;
-    dim3 grid(qtiles * n_splits, D.hkv, n_segs), cgrid(qtiles, D.hkv, n_segs);
+    dim3 grid(D.hkv, qtiles * n_splits, n_segs), cgrid(D.hkv, qtiles, n_segs);
     if (D.hd == 128) {
         attention_kernel<128, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, n_splits, part);
         if (n_splits > 1) attention_combine_kernel<128><<<cgrid, 256, 0, s>>>(D, part, Apk, mt_total, seg_base, n_splits);

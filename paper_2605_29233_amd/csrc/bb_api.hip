@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <algorithm>
 #include <string>
 #include <vector>
 
@@ -32,6 +33,7 @@ struct bb_ctx {
     int refresh_rows_cap, ngu;
     int force_nt[4], force_split[4];   // tuning overrides per epilogue kind (0 = heuristic)
     std::vector<HostReq> reqs;
+    std::vector<int> req_host, flags_host;   // request list as last uploaded (the caller's array is never read after the call returns)
     char* d_stats;                      // device staging for stats copies
     std::string err;
     int last_forward_rows, last_lm_cap;
@@ -153,6 +155,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.vr_part = b.take<float4>((size_t)lm_pad * 8);
     D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
     D.req_list = b.take<int>(l.max_requests);
+    D.req_flags = b.take<int>(l.max_requests);
     c->d_stats = b.take<char>(sizeof(ReqHeader) + sizeof(bb_branch_state) * BB_MAX_BRANCHES);
     D.Kc = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
     D.Vt = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
@@ -453,8 +456,13 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     return BB_OK;
 }
 
+// The list of requests a call works on lives on the device; it is copied only when it differs from the one the
+// previous call uploaded, and from a buffer the context owns.
 static int upload_req_list(bb_ctx* c, const int* ids, int n) {
-    HIPCHK(c, hipMemcpyAsync(c->D.req_list, ids, sizeof(int) * n, hipMemcpyHostToDevice, c->stream));
+    if ((int)c->req_host.size() == n && std::equal(ids, ids + n, c->req_host.begin())) return BB_OK;
+    c->req_host.assign(ids, ids + n);
+    HIPCHK(c, hipMemcpyAsync(c->D.req_list, c->req_host.data(), sizeof(int) * n, hipMemcpyHostToDevice, c->stream));
+    HIPCHK(c, hipStreamSynchronize(c->stream));      // the copy has left the host buffer before anything may change it
     return BB_OK;
 }
 
@@ -462,15 +470,25 @@ extern "C" int bb_refresh(bb_ctx* c, const int* ids, int n, int mode) {
     int rc = check_reqs(c, ids, n, mode == BB_PERIODIC);
     if (rc != BB_OK) return rc;
     if (mode != BB_INIT && mode != BB_PERIODIC) return fail(c, BB_EINVAL, "bad refresh mode");
-    for (int i = 0; i < n; ++i) {
-        HostReq& R = c->reqs[ids[i]];
-        if (mode == BB_INIT && R.initialised) return fail(c, BB_ESTATE, "request already initialised");
-        const int slot = ids[i];
-        launch_pack_refresh(c->D, slot, mode, c->stream);
-        if (mode == BB_INIT) rc = forward(c, R.L, R.G, 1, slot * c->D.max_br, 1, R.L, (R.L + BB_PAGE - 1) / BB_PAGE);
-        else rc = forward(c, R.N * R.L, 0, 2, slot * c->D.max_br, R.N, R.L, (R.L + BB_PAGE - 1) / BB_PAGE);
+    for (int i = 0; i < n; ++i)
+        if (mode == BB_INIT && c->reqs[ids[i]].initialised) return fail(c, BB_ESTATE, "request already initialised");
+    // The listed requests are packed into as few forwards as the activation buffers hold (they are sized for one
+    // request of the largest shape): consecutive requests share a forward while their rows fit.
+    const int rows_max = std::max(c->lim.max_step_rows, c->refresh_rows_cap), lm_max = c->D.lm_cap;
+    for (int i = 0; i < n;) {
+        int j = i, rows = 0, lm = 0, maxL = 0;
+        while (j < n) {
+            const HostReq& R = c->reqs[ids[j]];
+            const int r = mode == BB_INIT ? R.L : R.N * R.L, g = mode == BB_INIT ? R.G : 0;
+            if (j > i && (rows + r > rows_max || lm + g > lm_max)) break;
+            rows += r; lm += g; maxL = std::max(maxL, R.L); ++j;
+        }
+        if ((rc = upload_req_list(c, ids + i, j - i)) != BB_OK) return rc;
+        launch_pack_refresh(c->D, j - i, mode, c->stream);
+        rc = forward(c, rows, lm, mode == BB_INIT ? 1 : 2, 0, c->D.max_req * c->D.max_br, maxL, (maxL + BB_PAGE - 1) / BB_PAGE);
         if (rc != BB_OK) return rc;
-        if (mode == BB_INIT) R.initialised = 1;
+        if (mode == BB_INIT) for (int k = i; k < j; ++k) c->reqs[ids[k]].initialised = 1;
+        i = j;
     }
     return BB_OK;
 }
@@ -533,24 +551,39 @@ extern "C" int bb_generate(bb_ctx* c, const int* ids, int n, int max_block_forwa
     for (int i = 0; i < n; ++i)
         if (c->reqs[ids[i]].initialised) return fail(c, BB_ESTATE, "bb_generate wants requests that have not been initialised");
     std::vector<int> run(ids, ids + n), next, due;
-    auto poll = [&](const std::vector<int>& list) -> int {       // flags of the listed requests after a commit
+    int quiet = 1;                      // forwards that may run before any listed request needs a refresh
+    // One word per listed request after a commit (finished, refresh due, forwards left until a refresh is due), all
+    // read back with a single copy.
+    auto poll = [&](const std::vector<int>& list) -> int {
+        c->flags_host.resize(list.size());
         HIPCHK(c, hipStreamSynchronize(c->stream));
+        HIPCHK(c, hipMemcpy(c->flags_host.data(), c->D.req_flags, sizeof(int) * list.size(), hipMemcpyDeviceToHost));
         next.clear(); due.clear();
-        for (int id : list) {
-            ReqHeader h;
-            HIPCHK(c, hipMemcpy(&h, c->D.hdr + id, sizeof(h), hipMemcpyDeviceToHost));
-            if (!h.finished) { next.push_back(id); if (h.refresh_due) due.push_back(id); }
+        quiet = c->dc.refresh_interval;
+        for (size_t i = 0; i < list.size(); ++i) {
+            const int f = c->flags_host[i];
+            if (f & 1) continue;
+            next.push_back(list[i]);
+            if (f & 2) due.push_back(list[i]);             // refreshed before the next forward: a full interval ahead
+            else quiet = std::min(quiet, f >> 8);
         }
+        quiet = std::max(quiet, 1);
         return BB_OK;
     };
-    for (int id : run) if ((rc = bb_refresh(c, &id, 1, BB_INIT)) != BB_OK) return rc;
+    if ((rc = bb_refresh(c, run.data(), n, BB_INIT)) != BB_OK) return rc;
     if ((rc = bb_merge_commit(c, run.data(), n, nullptr)) != BB_OK) return rc;
     if ((rc = poll(run)) != BB_OK) return rc;
-    for (int fwd = 0; !next.empty() && fwd < max_block_forwards; ++fwd) {
+    for (int fwd = 0; !next.empty() && fwd < max_block_forwards;) {
         run = next;
         if (!due.empty() && (rc = bb_refresh(c, due.data(), (int)due.size(), BB_PERIODIC)) != BB_OK) return rc;
-        if ((rc = bb_denoise_step(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
-        if ((rc = bb_merge_commit(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
+        // No refresh can fall due during the next `quiet` forwards, so they are enqueued without reading anything
+        // back; a request that finishes on the way contributes no rows and counts no forward afterwards.
+        const int k = std::min(quiet, max_block_forwards - fwd);
+        for (int j = 0; j < k; ++j) {
+            if ((rc = bb_denoise_step(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
+            if ((rc = bb_merge_commit(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
+        }
+        fwd += k;
         if ((rc = poll(run)) != BB_OK) return rc;
     }
     if (stats) {
@@ -783,5 +816,43 @@ extern "C" int bb_debug_copy16(bb_ctx* c, const void* src_dev, void* dst_dev, si
     const size_t n = bytes / 16;
     copy16_kernel<<<(unsigned)std::min<size_t>((n + 255) / 256, 16384), 256, 0, c->stream>>>((const u32x4*)src_dev, (u32x4*)dst_dev, n);
     HIPCHK(c, hipGetLastError());
+    return BB_OK;
+}
+
+// ---- MFMA issue-rate reference ------------------------------------------------------------------------
+// Eight independent accumulator tiles per wave, one wave per SIMD, nothing but 32x32x16 bf16 MFMAs: what the matrix
+// pipes sustain on this chip at the clocks it holds under that load (the denominator beside the nominal peak).
+typedef __bf16 mr_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float mr_f32x16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float* __restrict__ out, int iters) {
+    mr_f32x16 acc[8];
+    for (int i = 0; i < 8; ++i) for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+    mr_bf16x8 a, b;
+    for (int j = 0; j < 8; ++j) { a[j] = (__bf16)(float)((threadIdx.x + j) & 3); b[j] = (__bf16)(float)(j & 1); }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 8; ++i) for (int r = 0; r < 16; ++r) s += acc[i][r];
+    out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+extern "C" int bb_debug_mfma_rate(bb_ctx* c, double* tflops_out_host) {
+    if (!c || !tflops_out_host) return BB_EINVAL;
+    const int wgs = 1024, iters = 40000;                     // 1024 x 256 floats of output fit the activation region easily
+    if ((size_t)wgs * 256 * sizeof(float) > (size_t)((char*)c->emb - (char*)c->h)) return fail(c, BB_ENOMEM, "activation region too small");
+    hipEvent_t e0, e1;
+    HIPCHK(c, hipEventCreate(&e0)); HIPCHK(c, hipEventCreate(&e1));
+    mfma_rate_kernel<<<wgs, 256, 0, c->stream>>>(c->h, iters);            // warm-up (clocks settle under the load)
+    HIPCHK(c, hipEventRecord(e0, c->stream));
+    mfma_rate_kernel<<<wgs, 256, 0, c->stream>>>(c->h, iters);
+    HIPCHK(c, hipEventRecord(e1, c->stream));
+    HIPCHK(c, hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    HIPCHK(c, hipGetLastError());
+    *tflops_out_host = (double)wgs * 4 * iters * 8 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
     return BB_OK;
 }

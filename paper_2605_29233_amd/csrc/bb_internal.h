@@ -60,6 +60,7 @@ struct Dev {
     float4* vr_part;            // [lm_cap][8] per-segment (max, sum, argmax) of the vocabulary reduction
     PageCopy* copies;           // [max_req*max_br*n_pages]
     int* req_list;              // [max_req] request slots of the current call
+    int* req_flags;             // [max_req] per listed request after a commit: bit 0 finished, bit 1 refresh due; bits 8.. forwards until a refresh is due
 };
 
 static inline __host__ __device__ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -135,7 +136,7 @@ void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int 
 void launch_vocab_reduce(const Dev& D, const float* logits, int lm_cap, int bcast, hipStream_t s);
 
 void launch_pack_step(const Dev& D, int n_req, hipStream_t s);
-void launch_pack_refresh(const Dev& D, int slot, int mode, hipStream_t s);
+void launch_pack_refresh(const Dev& D, int n_req, int mode, hipStream_t s);
 void launch_page_copies(const Dev& D, hipStream_t s);
 void launch_commit_merge(const Dev& D, int n_req, const uint16_t* lm_head, hipStream_t s);
 void launch_read_kv(const Dev& D, int phys_table_row_slot, int branch, int layer, float* K, float* V, int L,

@@ -95,65 +95,77 @@ __global__ __launch_bounds__(256) void pack_step_kernel(Dev D, int n_req) {
             }
         }
     }
-    if (t < n_req) {
+    if (t < n_req) {            // a request that has already finished contributes no rows and counts no forward
         ReqHeader& H = D.hdr[D.req_list[t]];
-        H.since_refresh += 1; H.nfe_block += 1;
+        if (!H.finished) { H.since_refresh += 1; H.nfe_block += 1; }
     }
 }
 
 void launch_pack_step(const Dev& D, int n_req, hipStream_t s) { pack_step_kernel<<<1, 256, 0, s>>>(D, n_req); }
 
-// Full-sequence forward of one request.  mode BB_INIT: the common row (all branches are still
-// identical), written to the request's shared physical row that every branch's page table
-// then points to; logits for the G generation positions.  mode BB_PERIODIC: all L rows of
-// every unfinished branch, each into its own physical row.
-__global__ __launch_bounds__(256) void pack_refresh_kernel(Dev D, int slot, int mode) {
-    __shared__ int s_off[BB_MAX_BRANCHES + 1];
+// Full-sequence forwards of the listed requests, packed into one row list.  mode BB_INIT: the common row of each
+// request (all its branches are still identical), written to the request's shared physical row that every branch's
+// page table then points to; logits for its G generation positions.  mode BB_PERIODIC: all L rows of every
+// unfinished branch, each into its own physical row.
+__global__ __launch_bounds__(256) void pack_refresh_kernel(Dev D, int n_req, int mode) {
+    __shared__ int s_off[256 + 1], s_lm[256 + 1];       // first packed row of each (listed request, branch); first LM row of each request
     const int nb_all = D.max_req * D.max_br, t = threadIdx.x;
-    ReqHeader& H = D.hdr[slot];
-    const int L = H.L, N = H.N;
     for (int i = t; i < nb_all; i += 256) D.seg_rows[i] = 0;
-    __syncthreads();
-    if (mode == BB_INIT) {
-        const int gbr = slot * D.max_br, shared_row = slot * D.phys_per_req + D.max_br;
-        const int* Xr = D.X + (size_t)gbr * D.lpad;
-        for (int i = t; i < L; i += 256) {
-            D.row_tok[i] = Xr[i]; D.row_pos[i] = i; D.row_gbr[i] = gbr; D.row_phys[i] = shared_row;
-        }
-        for (int j = t; j < H.G; j += 256) D.lm_row[j] = H.L_p + j;
-        for (int i = t; i < N * D.n_pages; i += 256)
-            D.table[(size_t)(gbr + i / D.n_pages) * D.n_pages + i % D.n_pages] = shared_row;
-        if (t == 0) {
-            D.seg_off[gbr] = 0; D.seg_rows[gbr] = L;
-            D.counts[0] = L; D.counts[1] = H.G; D.counts[2] = 0;
-            H.nfe_init += 1; H.since_refresh = 0; H.refresh_due = 0; H.initialised = 1;
-            for (int k = 0; k < BB_MAX_BRANCHES; ++k) H.pending[k] = k < N;
-        }
-        return;
-    }
     if (t == 0) {
-        int a = 0;
-        for (int k = 0; k < N; ++k) { s_off[k] = a; if (!D.br[slot * D.max_br + k].done) a += L; }
-        s_off[N] = a;
-        D.counts[0] = a; D.counts[1] = 0; D.counts[2] = 0;
-        H.nfe_refresh += 1; H.since_refresh = 0; H.refresh_due = 0;
+        int a = 0, lm = 0;
+        for (int i = 0; i < n_req; ++i) {
+            const int slot = D.req_list[i];
+            ReqHeader& H = D.hdr[slot];
+            s_lm[i] = lm;
+            for (int k = 0; k < D.max_br; ++k) {
+                s_off[i * D.max_br + k] = a;
+                if (mode == BB_INIT) { if (k == 0) a += H.L; }
+                else if (k < H.N && !D.br[slot * D.max_br + k].done) a += H.L;
+            }
+            if (mode == BB_INIT) {
+                lm += H.G;
+                H.nfe_init += 1; H.since_refresh = 0; H.refresh_due = 0; H.initialised = 1;
+                for (int k = 0; k < BB_MAX_BRANCHES; ++k) H.pending[k] = k < H.N;
+            } else {
+                H.nfe_refresh += 1; H.since_refresh = 0; H.refresh_due = 0;
+            }
+        }
+        s_off[n_req * D.max_br] = a;
+        D.counts[0] = a; D.counts[1] = lm; D.counts[2] = 0;
     }
     __syncthreads();
-    for (int k = 0; k < N; ++k) {
-        if (s_off[k + 1] == s_off[k]) continue;
-        const int gbr = slot * D.max_br + k, own = slot * D.phys_per_req + k;
-        const int* Xr = D.X + (size_t)gbr * D.lpad;
-        for (int i = t; i < L; i += 256) {
-            const int r = s_off[k] + i;
-            D.row_tok[r] = Xr[i]; D.row_pos[r] = i; D.row_gbr[r] = gbr; D.row_phys[r] = own;
+    for (int i = 0; i < n_req; ++i) {
+        const int slot = D.req_list[i];
+        const ReqHeader& H = D.hdr[slot];
+        const int L = H.L, N = H.N;
+        if (mode == BB_INIT) {
+            const int gbr = slot * D.max_br, shared_row = slot * D.phys_per_req + D.max_br, r0 = s_off[i * D.max_br];
+            const int* Xr = D.X + (size_t)gbr * D.lpad;
+            for (int j = t; j < L; j += 256) {
+                D.row_tok[r0 + j] = Xr[j]; D.row_pos[r0 + j] = j; D.row_gbr[r0 + j] = gbr; D.row_phys[r0 + j] = shared_row;
+            }
+            for (int j = t; j < H.G; j += 256) D.lm_row[s_lm[i] + j] = r0 + H.L_p + j;
+            for (int j = t; j < N * D.n_pages; j += 256)
+                D.table[(size_t)(gbr + j / D.n_pages) * D.n_pages + j % D.n_pages] = shared_row;
+            if (t == 0) { D.seg_off[gbr] = r0; D.seg_rows[gbr] = L; }
+            continue;
         }
-        for (int p = t; p < D.n_pages; p += 256) D.table[(size_t)gbr * D.n_pages + p] = own;
-        if (t == 0) { D.seg_off[gbr] = s_off[k]; D.seg_rows[gbr] = L; }
+        for (int k = 0; k < N; ++k) {
+            const int r0 = s_off[i * D.max_br + k];
+            if (s_off[i * D.max_br + k + 1] == r0) continue;
+            const int gbr = slot * D.max_br + k, own = slot * D.phys_per_req + k;
+            const int* Xr = D.X + (size_t)gbr * D.lpad;
+            for (int j = t; j < L; j += 256) {
+                D.row_tok[r0 + j] = Xr[j]; D.row_pos[r0 + j] = j; D.row_gbr[r0 + j] = gbr; D.row_phys[r0 + j] = own;
+            }
+            for (int pg = t; pg < D.n_pages; pg += 256) D.table[(size_t)gbr * D.n_pages + pg] = own;
+            if (t == 0) { D.seg_off[gbr] = r0; D.seg_rows[gbr] = L; }
+        }
     }
 }
 
-void launch_pack_refresh(const Dev& D, int slot, int mode, hipStream_t s) {
-    pack_refresh_kernel<<<1, 256, 0, s>>>(D, slot, mode);
+void launch_pack_refresh(const Dev& D, int n_req, int mode, hipStream_t s) {
+    pack_refresh_kernel<<<1, 256, 0, s>>>(D, n_req, mode);
 }
 
 // ---- page copies (copy-on-write before a block step, row copies after a sync) ------------------
@@ -303,7 +315,7 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
                 if (t == 0) { B[k].tokens_decoded = c; B[k].done = 1; B[k].start = B[k].end = L; }
             }
             if (t < BB_MAX_BRANCHES) H.pending[t] = 0;
-            if (t == 0) { H.finished = 2; H.winner = S.win; H.eos_pos = S.win_eos; H.all_done = 1; H.refresh_due = 0; }
+            if (t == 0) { H.finished = 2; H.winner = S.win; H.eos_pos = S.win_eos; H.all_done = 1; H.refresh_due = 0; D.req_flags[blockIdx.x] = 1; }
             return;
         }
     }
@@ -452,6 +464,12 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
             for (int i = L_p + t; i < L; i += 256) if (Xw[i] == D.eos_id) e = min(e, i);
         e = wg_min_i(e, S.si);
         if (t == 0) { H.finished = 1; H.winner = S.win; H.eos_pos = e == 0x7fffffff ? -1 : e; }
+    }
+    // one word per listed request for a driver loop: finished, refresh due, forwards left until a refresh falls due
+    if (t == 0) {
+        const int fin = H.finished != 0 || S.win >= 0;
+        const int left = max(0, D.refresh_interval - H.since_refresh);
+        D.req_flags[blockIdx.x] = fin | (H.refresh_due ? 2 : 0) | (left << 8);
     }
 }
 

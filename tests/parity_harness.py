@@ -248,6 +248,17 @@ class SideBySide:
         for d in (self._obs_conf, self._obs_pred):
             d.update({(k, i): v for (_, i), v in list(d.items()) for k in range(1, self.o.N)})
 
+    def check_init(self, view):
+        """The same comparison when several requests were initialised by one bb_refresh call."""
+        full = self.o.init_forward()
+        gbr, _ = view.rows()
+        mine = gbr // self.bb.limits.max_branches == self.rid
+        assert int(mine.sum()) == self.o.L
+        sel = np.nonzero(mine[view.lm_rows()])[0]
+        self._compare_forward(full, view, sel)
+        for d in (self._obs_conf, self._obs_pred):
+            d.update({(k, i): v for (_, i), v in list(d.items()) for k in range(1, self.o.N)})
+
     def step(self):
         self.oracle_step()
         self.check_step(self.bb.denoise_step([self.rid]))

@@ -200,6 +200,59 @@ def test_equal_rows_give_bit_identical_logits_wherever_they_are_placed():
         bb.close()
 
 
+def test_two_requests_initialised_and_refreshed_by_single_calls():
+    """Two requests of different lengths and branch sets share every forward: one bb_refresh(BB_INIT) call packs
+    both initial forwards, one bb_denoise_step both windows sets, one bb_refresh(BB_PERIODIC) both refreshes; each
+    is compared with its own oracle throughout."""
+    from paper_2605_29233_amd import BB_INIT, BB_PERIODIC
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 1))
+    om = OracleModel(w.model, weights, np.float64)
+    decode = DecodeParams(0.9, 0.5, 4, 3, 0)
+    bb = make_bb(w.model, decode, weights, 3, 70 + 48, 48, 96, max_requests=2)      # 96 >= 48 + 40 logit rows: both initial forwards fit one call
+    try:
+        a = SideBySide(bb, om, gen_prompt(w.model, 1, 0, 70), 48, (8, 16, 32), decode, conf_tol=5e-4)
+        b = SideBySide(bb, om, gen_prompt(w.model, 1, 1, 37), 40, (4, 16), decode, conf_tol=5e-4)
+        ids = [a.rid, b.rid]
+        bb.refresh(ids, BB_INIT)
+        view = bb.latest_view()
+        assert view.m_q == a.o.L + b.o.L and view.m_lm == 48 + 40
+        for s in (a, b):
+            s.check_init(view)
+            for k in range(s.o.N):
+                s.compare_kv(k, w.model.n_layers - 1)
+            s.oracle_commit()
+        st = bb.merge_commit(ids)
+        a.check_commit(st[0]); b.check_commit(st[1])
+        refreshes = 0
+        for step in range(10):
+            run = [s for s in (a, b) if not s.o.finished]
+            if not run:
+                break
+            due = [s for s in run if s.o.refresh_due]
+            if due:
+                bb.refresh([s.rid for s in due], BB_PERIODIC)
+                for s in due:
+                    s.o.refresh()
+                    s.compare_kv(0, w.model.n_layers - 1)
+                refreshes += len(due) == 2
+            for s in run:
+                s.oracle_step()
+            view = bb.denoise_step([s.rid for s in run])
+            for s in run:
+                s.check_step(view)
+                s.oracle_commit()
+            st = bb.merge_commit([s.rid for s in run])
+            for s, x in zip(run, st):
+                s.check_commit(x)
+        assert refreshes >= 1                       # at least one call refreshed both requests together
+        print("two requests:", a.rep, "|", b.rep, flush=True)
+        for s in (a, b):
+            assert s.rep.max_logit_err <= 3e-2 and s.rep.asserted_steps == s.rep.commit_steps
+    finally:
+        bb.close()
+
+
 def test_eos_ready_after_the_initial_commit_waits_for_the_loop():
     """Alg. 1 has CheckEOS inside its while loop only.  With seed 0 the initial commit of the tiny workload fills
     the first generation position of every branch; taking that token as the EOS id makes all three branches
