@@ -1,23 +1,23 @@
 """Drives the CPU oracle and the HIP library side by side, teacher-forced.
 
 Before every GPU call the token / window / counter state of the two sides is equal.  Comparison bar:
-  * logits: max-abs <= 3e-2 over every row that received logits (mask column excluded); top-1
-    confidence within 5e-3; argmax equal wherever the oracle's top-1 / top-2 logit margin exceeds 1e-2;
-  * commit, merge, sync, window, done, counter, EOS and winner results: bit-exact, decision by decision.
-    A floating-point decision of the oracle that lies within a guard band of flipping is allowed to fall
-    either way.  The band is 1e-2 for a value against a threshold (a confidence against tau_dec, a merge
-    probability against tau_merge), for competing merge sources and for an argmax over near-equal
-    logits; two confidences compared with each other (the arg max that picks i*, competing leaders'
-    mean confidences) can only swap if they are closer than twice the per-value tolerance that
-    the forward comparison asserts (conf_tol), so that is their band:
-    an in-band Eq. 1 decision (threshold, i*, argmax token) is taken the way the library's own reported
-    confidence / argmax of that row says (which also checks that its commits are consistent with what it
-    reports); for the remaining in-band decisions (leader, merge acceptance, merge source) the oracle's
-    policy is run once per combination ("worlds"; usually there is exactly one) and the GPU's complete
-    state after the commit must equal the complete state of one of them.  Everything a guard-band decision cannot reach is therefore asserted exactly, in every
-    step, and what it can reach must still be a consistent outcome of the algorithm.  When the GPU
-    took an in-band decision the other way, the oracle continues from that world (same tokens, same
-    cache-row copies), so both sides stay comparable without rewriting GPU state.
+  * logits: max-abs <= 3e-2 over every row that received logits (mask column excluded); top-1 confidence
+    within conf_tol (5e-3, tighter where the oracle runs in fp64); argmax equal wherever the oracle's
+    top-1 / top-2 logit margin exceeds 1e-2, and one of the near-top tokens otherwise;
+  * commit, merge, sync, window, done, counter, EOS and winner results: bit-exact.  After every commit the
+    library's complete state (token rows, windows, done flags, all counters, finished / winner / EOS
+    position, NFE) must equal the oracle's complete state.  A floating-point decision of the oracle that
+    lies within a guard band of flipping may fall either way: 1e-2 for a value against a threshold (a
+    confidence against tau_dec, a merge probability against tau_merge), for competing merge sources and
+    for an argmax over near-equal logits; two confidences compared with each other (the arg max that picks
+    i*, competing leaders' mean confidences) can only swap if they are closer than twice conf_tol, so that
+    is their band.  The oracle's policy is run with such decisions taken the way the library visibly took
+    them (its reported confidence of the row, the token the destination holds afterwards, the row a
+    laggard was copied from) and, where nothing shows it, once per remaining combination; a commit passes
+    only if one of these runs reproduces the library's complete state.  Every decision outside the bands is
+    thereby asserted exactly, in every step, and the in-band ones must still form a consistent outcome of
+    the algorithm.  The oracle continues from the accepted outcome (same tokens, same cache-row copies),
+    so both sides stay comparable without rewriting GPU state.
 """
 import copy
 from types import SimpleNamespace
