@@ -15,7 +15,7 @@
  *
  * Conventions
  *   - Every call returns 0 (BB_OK) or a negative error code; bb_last_error() gives a text.
- *     Nothing throws or aborts across this boundary.
+ *     Nothing throws or aborts across this boundary (a failed host allocation inside a call is BB_ENOMEM).
  *   - All device work is enqueued on the HIP stream given to bb_create and is asynchronous,
  *     except where a call copies results to host memory (stated per call).
  *   - The library allocates no device memory: the caller passes one workspace of at least

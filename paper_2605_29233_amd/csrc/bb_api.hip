@@ -5,6 +5,8 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
+#include <new>
 #include <algorithm>
 #include <string>
 #include <vector>
@@ -202,27 +204,30 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
 }
 
 extern "C" size_t bb_workspace_bytes(const bb_model_cfg* model, const bb_limits* limits) {
-    if (check_cfg(model, limits, nullptr) != BB_OK) return 0;
-    bb_ctx tmp{};
-    tmp.m = *model; tmp.lim = *limits; tmp.dc = bb_decode_cfg{};
-    size_t total = 0;
-    layout(&tmp, nullptr, &total);
-    return total;
+    try {
+        if (check_cfg(model, limits, nullptr) != BB_OK) return 0;
+        bb_ctx tmp{};
+        tmp.m = *model; tmp.lim = *limits; tmp.dc = bb_decode_cfg{};
+        size_t total = 0;
+        layout(&tmp, nullptr, &total);
+        return total;
+    } catch (...) { return 0; }
 }
 
-extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decode_cfg* decode,
-                         const bb_limits* limits, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+static int bb_create_impl(bb_ctx** out, const bb_model_cfg* model, const bb_decode_cfg* decode,
+                          const bb_limits* limits, void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
     if (!out || !decode || !workspace_dev) return BB_EINVAL;
     std::string why;
     if (check_cfg(model, limits, &why) != BB_OK) return BB_EINVAL;
     if (decode->refresh_interval < 1) return BB_EINVAL;
     if (reinterpret_cast<uintptr_t>(workspace_dev) % 256) return BB_EINVAL;
-    bb_ctx* c = new bb_ctx{};
+    std::unique_ptr<bb_ctx> holder(new bb_ctx{});          // released to the caller only when everything succeeded
+    bb_ctx* c = holder.get();
     c->m = *model; c->dc = *decode; c->lim = *limits;
     c->stream = (hipStream_t)hip_stream;
     size_t total = 0;
     layout(c, (char*)workspace_dev, &total);
-    if (total > workspace_bytes) { delete c; return BB_ENOMEM; }
+    if (total > workspace_bytes) return BB_ENOMEM;
     c->ws = (char*)workspace_dev; c->ws_bytes = workspace_bytes;
     c->reqs.assign(limits->max_requests, HostReq{});
     c->n_expected = 3 + model->n_layers * (model->qkv_bias ? 12 : 9);
@@ -231,13 +236,13 @@ extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decod
     // otherwise reach 0 * NaN in the attention's P.V product)
     size_t zero_bytes = (char*)c->emb - c->ws;
     hipError_t e = hipMemsetAsync(c->ws, 0, zero_bytes, c->stream);
-    if (e != hipSuccess) { delete c; return BB_EHIP; }
+    if (e != hipSuccess) return BB_EHIP;
     if (model->d_ffn % 64)            // padded gate/up rows and the down projection's padded k columns must be zero
         for (auto& L : c->layers) {
             if (e == hipSuccess) e = hipMemsetAsync(L.wgu, 0, (size_t)c->ngu * model->d_model * 2, c->stream);
             if (e == hipSuccess) e = hipMemsetAsync(L.wdown, 0, (size_t)model->d_model * ((model->d_ffn + 63) / 64 * 64) * 2, c->stream);
         }
-    if (e != hipSuccess) { delete c; return BB_EHIP; }
+    if (e != hipSuccess) return BB_EHIP;
     // rotary table in double precision on the host
     const int half = model->head_dim / 2, lpad = c->D.lpad;
     std::vector<float> cs((size_t)lpad * half), sn((size_t)lpad * half);
@@ -250,12 +255,12 @@ extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decod
     e = hipMemcpyAsync(c->D.rope_cos, cs.data(), cs.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(c->D.rope_sin, sn.data(), sn.size() * 4, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-    if (e != hipSuccess) { delete c; return BB_EHIP; }
-    *out = c;
+    if (e != hipSuccess) return BB_EHIP;
+    *out = holder.release();
     return BB_OK;
 }
 
-extern "C" int bb_destroy(bb_ctx* ctx) {
+static int bb_destroy_impl(bb_ctx* ctx) {
     if (!ctx) return BB_EINVAL;
     (void)hipStreamSynchronize(ctx->stream);
     for (auto& r : ctx->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
@@ -332,7 +337,7 @@ static int load_one(bb_ctx* c, const bb_tensor& t) {
     return BB_OK;
 }
 
-extern "C" int bb_load_weights(bb_ctx* ctx, const bb_tensor* tensors, int n) {
+static int bb_load_weights_impl(bb_ctx* ctx, const bb_tensor* tensors, int n) {
     if (!ctx || !tensors || n < 0) return BB_EINVAL;
     for (int i = 0; i < n; ++i) {
         int rc = load_one(ctx, tensors[i]);
@@ -349,7 +354,7 @@ static bool weights_complete(const bb_ctx* c) {
 }
 
 // ---- requests ---------------------------------------------------------------------------------------
-extern "C" int bb_request_open(bb_ctx* c, const int32_t* prompt, int L_p, int G, const int* blocks, int N, int* req_id) {
+static int bb_request_open_impl(bb_ctx* c, const int32_t* prompt, int L_p, int G, const int* blocks, int N, int* req_id) {
     if (!c || !prompt || !blocks || !req_id) return BB_EINVAL;
     if (L_p < 1 || G < 1 || N < 1) return fail(c, BB_EINVAL, "bad request shape");
     if (N > c->lim.max_branches || L_p + G > c->lim.max_seq_len || G > c->lim.max_gen_len)
@@ -383,7 +388,7 @@ extern "C" int bb_request_open(bb_ctx* c, const int32_t* prompt, int L_p, int G,
     return BB_OK;
 }
 
-extern "C" int bb_request_close(bb_ctx* c, int req_id) {
+static int bb_request_close_impl(bb_ctx* c, int req_id) {
     if (!c || req_id < 0 || req_id >= c->lim.max_requests || !c->reqs[req_id].in_use) return BB_EINVAL;
     HIPCHK(c, hipMemsetAsync(c->D.hdr + req_id, 0, sizeof(ReqHeader), c->stream));
     c->reqs[req_id].in_use = 0;
@@ -466,7 +471,7 @@ static int upload_req_list(bb_ctx* c, const int* ids, int n) {
     return BB_OK;
 }
 
-extern "C" int bb_refresh(bb_ctx* c, const int* ids, int n, int mode) {
+static int bb_refresh_impl(bb_ctx* c, const int* ids, int n, int mode) {
     int rc = check_reqs(c, ids, n, mode == BB_PERIODIC);
     if (rc != BB_OK) return rc;
     if (mode != BB_INIT && mode != BB_PERIODIC) return fail(c, BB_EINVAL, "bad refresh mode");
@@ -500,7 +505,7 @@ static void fill_view(bb_ctx* c, bb_step_view* v) {
     v->rows_capacity = D.lm_cap;
 }
 
-extern "C" int bb_denoise_step(bb_ctx* c, const int* ids, int n, bb_step_view* view) {
+static int bb_denoise_step_impl(bb_ctx* c, const int* ids, int n, bb_step_view* view) {
     int rc = check_reqs(c, ids, n, true);
     if (rc != BB_OK) return rc;
     int rows = 0, maxb = 0, maxL = 0;
@@ -530,7 +535,7 @@ static int read_stats(bb_ctx* c, int slot, bb_request_stats* out) {
     return BB_OK;
 }
 
-extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stats* stats) {
+static int bb_merge_commit_impl(bb_ctx* c, const int* ids, int n, bb_request_stats* stats) {
     int rc = check_reqs(c, ids, n, true);
     if (rc != BB_OK) return rc;
     if ((rc = upload_req_list(c, ids, n)) != BB_OK) return rc;
@@ -544,7 +549,7 @@ extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stat
 }
 
 // ---- Alg. 1 driver --------------------------------------------------------------------------------------
-extern "C" int bb_generate(bb_ctx* c, const int* ids, int n, int max_block_forwards, bb_request_stats* stats) {
+static int bb_generate_impl(bb_ctx* c, const int* ids, int n, int max_block_forwards, bb_request_stats* stats) {
     int rc = check_reqs(c, ids, n, false);
     if (rc != BB_OK) return rc;
     if (max_block_forwards < 0) return fail(c, BB_EINVAL, "max_block_forwards must not be negative");
@@ -570,18 +575,18 @@ extern "C" int bb_generate(bb_ctx* c, const int* ids, int n, int max_block_forwa
         quiet = std::max(quiet, 1);
         return BB_OK;
     };
-    if ((rc = bb_refresh(c, run.data(), n, BB_INIT)) != BB_OK) return rc;
-    if ((rc = bb_merge_commit(c, run.data(), n, nullptr)) != BB_OK) return rc;
+    if ((rc = bb_refresh_impl(c, run.data(), n, BB_INIT)) != BB_OK) return rc;
+    if ((rc = bb_merge_commit_impl(c, run.data(), n, nullptr)) != BB_OK) return rc;
     if ((rc = poll(run)) != BB_OK) return rc;
     for (int fwd = 0; !next.empty() && fwd < max_block_forwards;) {
         run = next;
-        if (!due.empty() && (rc = bb_refresh(c, due.data(), (int)due.size(), BB_PERIODIC)) != BB_OK) return rc;
+        if (!due.empty() && (rc = bb_refresh_impl(c, due.data(), (int)due.size(), BB_PERIODIC)) != BB_OK) return rc;
         // No refresh can fall due during the next `quiet` forwards, so they are enqueued without reading anything
         // back; a request that finishes on the way contributes no rows and counts no forward afterwards.
         const int k = std::min(quiet, max_block_forwards - fwd);
         for (int j = 0; j < k; ++j) {
-            if ((rc = bb_denoise_step(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
-            if ((rc = bb_merge_commit(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
+            if ((rc = bb_denoise_step_impl(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
+            if ((rc = bb_merge_commit_impl(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
         }
         fwd += k;
         if ((rc = poll(run)) != BB_OK) return rc;
@@ -599,19 +604,19 @@ static int check_one(bb_ctx* c, int id) {
     return BB_OK;
 }
 
-extern "C" int bb_debug_set_gemm_plan(bb_ctx* c, int kind, int nt, int split_k) {
+static int bb_debug_set_gemm_plan_impl(bb_ctx* c, int kind, int nt, int split_k) {
     if (!c || kind < 0 || kind > 3 || nt < 0 || nt > 2 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     c->force_nt[kind] = nt; c->force_split[kind] = split_k;
     return BB_OK;
 }
 
-extern "C" int bb_profile_enable(bb_ctx* c, int on) {
+static int bb_profile_enable_impl(bb_ctx* c, int on) {
     if (!c) return BB_EINVAL;
     c->prof_on = on != 0;
     return BB_OK;
 }
 
-extern "C" int bb_profile_read(bb_ctx* c, bb_profile_entry* out, int max_entries, int* n_out) {
+static int bb_profile_read_impl(bb_ctx* c, bb_profile_entry* out, int max_entries, int* n_out) {
     if (!c || !out || !n_out || max_entries < 1) return BB_EINVAL;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     bb_profile_entry acc[BB_K_CLASSES];
@@ -632,26 +637,26 @@ extern "C" int bb_profile_read(bb_ctx* c, bb_profile_entry* out, int max_entries
     return BB_OK;
 }
 
-extern "C" int bb_synchronize(bb_ctx* c) {
+static int bb_synchronize_impl(bb_ctx* c) {
     if (!c) return BB_EINVAL;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     return BB_OK;
 }
 
-extern "C" int bb_read_device(bb_ctx* c, const void* src, void* dst, size_t bytes) {
+static int bb_read_device_impl(bb_ctx* c, const void* src, void* dst, size_t bytes) {
     if (!c || !src || !dst) return BB_EINVAL;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     HIPCHK(c, hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost));
     return BB_OK;
 }
 
-extern "C" int bb_get_view(bb_ctx* c, bb_step_view* view) {
+static int bb_get_view_impl(bb_ctx* c, bb_step_view* view) {
     if (!c || !view) return BB_EINVAL;
     fill_view(c, view);
     return BB_OK;
 }
 
-extern "C" int bb_get_tokens(bb_ctx* c, int id, int32_t* X) {
+static int bb_get_tokens_impl(bb_ctx* c, int id, int32_t* X) {
     if (check_one(c, id) != BB_OK || !X) return BB_EINVAL;
     const HostReq& R = c->reqs[id];
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -660,13 +665,13 @@ extern "C" int bb_get_tokens(bb_ctx* c, int id, int32_t* X) {
     return BB_OK;
 }
 
-extern "C" int bb_get_stats(bb_ctx* c, int id, bb_request_stats* out) {
+static int bb_get_stats_impl(bb_ctx* c, int id, bb_request_stats* out) {
     if (check_one(c, id) != BB_OK || !out) return BB_EINVAL;
     HIPCHK(c, hipStreamSynchronize(c->stream));
     return read_stats(c, id, out);
 }
 
-extern "C" int bb_set_state(bb_ctx* c, int id, const int32_t* X, const bb_branch_state* brs) {
+static int bb_set_state_impl(bb_ctx* c, int id, const int32_t* X, const bb_branch_state* brs) {
     if (check_one(c, id) != BB_OK || !X || !brs) return BB_EINVAL;
     const HostReq& R = c->reqs[id];
     HIPCHK(c, hipStreamSynchronize(c->stream));
@@ -686,7 +691,7 @@ extern "C" int bb_set_state(bb_ctx* c, int id, const int32_t* X, const bb_branch
     return BB_OK;
 }
 
-extern "C" int bb_get_kv(bb_ctx* c, int id, int branch, int layer, float* K, float* V) {
+static int bb_get_kv_impl(bb_ctx* c, int id, int branch, int layer, float* K, float* V) {
     if (check_one(c, id) != BB_OK || !K || !V) return BB_EINVAL;
     const HostReq& R = c->reqs[id];
     if (branch < 0 || branch >= R.N || layer < 0 || layer >= c->m.n_layers) return BB_EINVAL;
@@ -699,7 +704,7 @@ extern "C" int bb_get_kv(bb_ctx* c, int id, int branch, int layer, float* K, flo
     return BB_OK;
 }
 
-extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
+static int bb_debug_gemm_impl(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
     if (!c || !A || !W || !C || M < 1 || N < 32 || K < 16 || N % 32 || K % 16 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     const int mt = (M + 31) / 32, rows_pad = mt * 32;
     GemmPlan p = gemm_plan(M, N, K, split_k, 0);
@@ -733,7 +738,7 @@ extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float
 }
 
 // ---- KV-consistency diagnostics -----------------------------------------------------------------------
-extern "C" size_t bb_kv_diag_scratch_bytes(bb_ctx* c, int id) {
+extern "C" size_t bb_kv_diag_scratch_bytes(bb_ctx* c, int id) {      // no allocation, nothing to throw
     if (check_one(c, id) != BB_OK) return 0;
     const HostReq& R = c->reqs[id];
     const size_t pages = (R.L + BB_PAGE - 1) / BB_PAGE;
@@ -741,7 +746,7 @@ extern "C" size_t bb_kv_diag_scratch_bytes(bb_ctx* c, int id) {
     return 2 * row * R.N + align_up((size_t)c->m.n_layers * pages * sizeof(double), 256);     // K and V snapshots + partial sums
 }
 
-extern "C" int bb_kv_diagnostics(bb_ctx* c, int id, void* scratch, size_t scratch_bytes, double* E, double* Dpair, double* Davg) {
+static int bb_kv_diagnostics_impl(bb_ctx* c, int id, void* scratch, size_t scratch_bytes, double* E, double* Dpair, double* Davg) {
     if (check_one(c, id) != BB_OK) return BB_EINVAL;
     const HostReq& R = c->reqs[id];
     if (!R.initialised) return fail(c, BB_ESTATE, "request has not had its initial refresh");
@@ -790,7 +795,7 @@ extern "C" int bb_kv_diagnostics(bb_ctx* c, int id, void* scratch, size_t scratc
             launch_kv_snapshot(c->D, g0 + k, snapK, snapV, R.N, k, pages, c->stream);
         }
         if (any) {
-            if ((rc = bb_refresh(c, &id, 1, BB_PERIODIC)) != BB_OK) return rc;
+            if ((rc = bb_refresh_impl(c, &id, 1, BB_PERIODIC)) != BB_OK) return rc;
             for (int k = 0; k < R.N; ++k) {
                 if (br[k].done) continue;
                 launch_kv_sqdist(c->D, g0 + k, 0, snapK, snapV, R.N, k, pages, part, c->stream);
@@ -809,7 +814,7 @@ __global__ __launch_bounds__(256) void copy16_kernel(const u32x4* __restrict__ s
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
 
-extern "C" int bb_debug_copy16(bb_ctx* c, const void* src_dev, void* dst_dev, size_t bytes) {
+static int bb_debug_copy16_impl(bb_ctx* c, const void* src_dev, void* dst_dev, size_t bytes) {
     if (!c || !src_dev || !dst_dev) return BB_EINVAL;
     if (bytes % 16 || (uintptr_t)src_dev % 16 || (uintptr_t)dst_dev % 16) return fail(c, BB_EINVAL, "bb_debug_copy16: arguments must be multiples of 16");
     if (bytes == 0) return BB_OK;
@@ -838,7 +843,7 @@ __global__ __launch_bounds__(256, 1) void mfma_rate_kernel(float* __restrict__ o
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
-extern "C" int bb_debug_mfma_rate(bb_ctx* c, double* tflops_out_host) {
+static int bb_debug_mfma_rate_impl(bb_ctx* c, double* tflops_out_host) {
     if (!c || !tflops_out_host) return BB_EINVAL;
     const int wgs = 1024, iters = 40000;                     // 1024 x 256 floats of output fit the activation region easily
     if ((size_t)wgs * 256 * sizeof(float) > (size_t)((char*)c->emb - (char*)c->h)) return fail(c, BB_ENOMEM, "activation region too small");
@@ -855,4 +860,105 @@ extern "C" int bb_debug_mfma_rate(bb_ctx* c, double* tflops_out_host) {
     HIPCHK(c, hipGetLastError());
     *tflops_out_host = (double)wgs * 4 * iters * 8 * (2.0 * 32 * 32 * 16) / (ms * 1e-3) / 1e12;
     return BB_OK;
+}
+
+// ---- the boundary proper: nothing throws across it ----------------------------------------------------------
+// The host code above uses std::vector / std::string; an allocation failure there becomes BB_ENOMEM here.
+#define BB_GUARD(ctx, call) \
+    try { return call; } \
+    catch (const std::bad_alloc&) { bb_ctx* c_ = const_cast<bb_ctx*>(static_cast<const bb_ctx*>(ctx)); \
+                                    if (c_) { try { c_->err = "out of host memory"; } catch (...) {} } return BB_ENOMEM; } \
+    catch (...) { return BB_EINVAL; }
+
+extern "C" int bb_destroy(bb_ctx* ctx) {
+    BB_GUARD(ctx, bb_destroy_impl(ctx));
+}
+
+extern "C" int bb_load_weights(bb_ctx* ctx, const bb_tensor* tensors, int n) {
+    BB_GUARD(ctx, bb_load_weights_impl(ctx, tensors, n));
+}
+
+extern "C" int bb_request_open(bb_ctx* c, const int32_t* prompt, int L_p, int G, const int* blocks, int N, int* req_id) {
+    BB_GUARD(c, bb_request_open_impl(c, prompt, L_p, G, blocks, N, req_id));
+}
+
+extern "C" int bb_request_close(bb_ctx* c, int req_id) {
+    BB_GUARD(c, bb_request_close_impl(c, req_id));
+}
+
+extern "C" int bb_refresh(bb_ctx* c, const int* ids, int n, int mode) {
+    BB_GUARD(c, bb_refresh_impl(c, ids, n, mode));
+}
+
+extern "C" int bb_denoise_step(bb_ctx* c, const int* ids, int n, bb_step_view* view) {
+    BB_GUARD(c, bb_denoise_step_impl(c, ids, n, view));
+}
+
+extern "C" int bb_merge_commit(bb_ctx* c, const int* ids, int n, bb_request_stats* stats) {
+    BB_GUARD(c, bb_merge_commit_impl(c, ids, n, stats));
+}
+
+extern "C" int bb_generate(bb_ctx* c, const int* ids, int n, int max_block_forwards, bb_request_stats* stats) {
+    BB_GUARD(c, bb_generate_impl(c, ids, n, max_block_forwards, stats));
+}
+
+extern "C" int bb_debug_set_gemm_plan(bb_ctx* c, int kind, int nt, int split_k) {
+    BB_GUARD(c, bb_debug_set_gemm_plan_impl(c, kind, nt, split_k));
+}
+
+extern "C" int bb_profile_enable(bb_ctx* c, int on) {
+    BB_GUARD(c, bb_profile_enable_impl(c, on));
+}
+
+extern "C" int bb_profile_read(bb_ctx* c, bb_profile_entry* out, int max_entries, int* n_out) {
+    BB_GUARD(c, bb_profile_read_impl(c, out, max_entries, n_out));
+}
+
+extern "C" int bb_synchronize(bb_ctx* c) {
+    BB_GUARD(c, bb_synchronize_impl(c));
+}
+
+extern "C" int bb_read_device(bb_ctx* c, const void* src, void* dst, size_t bytes) {
+    BB_GUARD(c, bb_read_device_impl(c, src, dst, bytes));
+}
+
+extern "C" int bb_get_view(bb_ctx* c, bb_step_view* view) {
+    BB_GUARD(c, bb_get_view_impl(c, view));
+}
+
+extern "C" int bb_get_tokens(bb_ctx* c, int id, int32_t* X) {
+    BB_GUARD(c, bb_get_tokens_impl(c, id, X));
+}
+
+extern "C" int bb_get_stats(bb_ctx* c, int id, bb_request_stats* out) {
+    BB_GUARD(c, bb_get_stats_impl(c, id, out));
+}
+
+extern "C" int bb_set_state(bb_ctx* c, int id, const int32_t* X, const bb_branch_state* brs) {
+    BB_GUARD(c, bb_set_state_impl(c, id, X, brs));
+}
+
+extern "C" int bb_get_kv(bb_ctx* c, int id, int branch, int layer, float* K, float* V) {
+    BB_GUARD(c, bb_get_kv_impl(c, id, branch, layer, K, V));
+}
+
+extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
+    BB_GUARD(c, bb_debug_gemm_impl(c, A, W, C, M, N, K, split_k));
+}
+
+extern "C" int bb_kv_diagnostics(bb_ctx* c, int id, void* scratch, size_t scratch_bytes, double* E, double* Dpair, double* Davg) {
+    BB_GUARD(c, bb_kv_diagnostics_impl(c, id, scratch, scratch_bytes, E, Dpair, Davg));
+}
+
+extern "C" int bb_debug_copy16(bb_ctx* c, const void* src_dev, void* dst_dev, size_t bytes) {
+    BB_GUARD(c, bb_debug_copy16_impl(c, src_dev, dst_dev, bytes));
+}
+
+extern "C" int bb_debug_mfma_rate(bb_ctx* c, double* tflops_out_host) {
+    BB_GUARD(c, bb_debug_mfma_rate_impl(c, tflops_out_host));
+}
+
+extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decode_cfg* decode, const bb_limits* limits,
+                         void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
+    BB_GUARD(nullptr, bb_create_impl(out, model, decode, limits, workspace_dev, workspace_bytes, hip_stream));
 }
