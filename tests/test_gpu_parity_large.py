@@ -16,8 +16,11 @@ from parity_harness import SideBySide, make_bb
 pytestmark = pytest.mark.gpu
 
 
-def setup(name, n_sample=None):
+def setup(name, decode=None):
     w = workload(name)
+    if decode is not None:
+        import dataclasses
+        w = dataclasses.replace(w, decode=decode)
     t = time.time()
     weights = dict(gen_weights(w.model, w.seed, device="cuda:0"))
     L = max(w.prompt_lens) + w.gen_len
@@ -32,8 +35,8 @@ def setup(name, n_sample=None):
     return w, bb, om
 
 
-def single_request(name, steps, refresh_after=None):
-    w, bb, om = setup(name)
+def single_request(name, steps, refresh_after=None, decode=None, check_synced_rows=False):
+    w, bb, om = setup(name, decode)
     try:
         prompt = gen_prompt(w.model, w.seed, 0, w.prompt_lens[0])
         s = SideBySide(bb, om, prompt, w.gen_len, w.block_sizes, w.decode)
@@ -42,14 +45,18 @@ def single_request(name, steps, refresh_after=None):
         print(f"[{name}] init compared in {time.time() - t:.1f}s: {s.rep}", flush=True)
         s.compare_kv(0, 0)
         s.compare_kv(len(w.block_sizes) - 1, w.model.n_layers - 1)
-        s.commit()
+        info = s.commit()
         for i in range(steps):
+            if check_synced_rows:
+                for d, lead in info["syncs"]:          # the laggard's cache row is now the leader's, page for page
+                    s.compare_kv(d, 0)
+                    s.compare_kv(d, w.model.n_layers - 1)
             if s.o.refresh_due or i == refresh_after:
                 s.refresh()
                 s.compare_kv(0, w.model.n_layers - 1)
             t = time.time()
             s.step()
-            s.commit()
+            info = s.commit()
             print(f"[{name}] step {i} compared in {time.time() - t:.1f}s: {s.rep}", flush=True)
         assert s.rep.max_logit_err <= 3e-2
         # every commit above was matched against the admissible outcomes (the harness raises otherwise)
@@ -61,6 +68,15 @@ def single_request(name, steps, refresh_after=None):
 
 def test_llada_8b_shape():
     single_request("llada", steps=3, refresh_after=2)
+
+
+def test_llada_8b_shape_with_leader_syncs():
+    """tau_sync = 1 makes laggards copy the leader after the first commits: token rows, page tables (shared and
+    private pages of 403 MB rows) and probability maps move at the full shape, and the next block forward of the
+    copied branch must still match the oracle's."""
+    from workload.configs import DecodeParams
+    s = single_request("llada", steps=3, decode=DecodeParams(tau_sync=1, refresh_interval=8), check_synced_rows=True)
+    assert s.rep.syncs >= 2, s.rep
 
 
 def test_dream_7b_shape():
