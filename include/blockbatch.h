@@ -113,7 +113,9 @@ typedef struct {
     const int*   argmax_dev;       /* [M_lm] top-1 token                                    */
     const float* conf_dev;         /* [M_lm] top-1 probability                              */
     const float* lse_dev;          /* [M_lm] log-sum-exp of the row's logits                */
-    const float* logits_dev;       /* [M_lm][vocab] fp32, mask column as computed (ignore)  */
+    const float* logits_dev;       /* [M_lm][vocab] fp32, mask column as computed (ignore); NULL unless
+                                      bb_debug_keep_logits is on: the LM head reduces the logits of a row
+                                      to (max, sum, argmax) in its epilogue and does not store them        */
     int rows_capacity;
 } bb_step_view;
 
@@ -247,8 +249,12 @@ int bb_debug_gemm(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, floa
 int bb_gemm_static(const float* A_dev, const uint16_t* W_dev, float* C_dev, int M, int N, int K, int split_k,
                    void* hip_stream);
 
+/* Tests: on != 0 makes every later forward also store the fp32 logits of the rows that receive them (view's
+ * logits_dev); off (the default) the logits exist only in the registers of the LM-head GEMM. */
+int bb_debug_keep_logits(bb_ctx* ctx, int on);
+
 /* Tuning knob: override the tile width (nt = 1: 128 columns, 2: 256; 0 = heuristic) and the
- * split-K factor (0 = heuristic) of one GEMM kind (0 LM head, 1 O/down, 2 gate/up, 3 QKV) for
+ * split-K factor (0 = heuristic) of one GEMM kind (1 O/down, 2 gate/up, 3 QKV; 0, the LM head, is fixed) for
  * panels of at most 128 rows.  Results are unchanged up to fp32 summation order. */
 int bb_debug_set_gemm_plan(bb_ctx* ctx, int kind, int nt, int split_k);
 

@@ -64,7 +64,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate", "bb_debug_keep_logits")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -109,6 +109,7 @@ def load_library():
         lib.bb_kv_diagnostics.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
         lib.bb_generate.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         lib.bb_debug_copy16.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
+        lib.bb_debug_keep_logits.argtypes = [C.c_void_p, C.c_int]
         lib.bb_debug_mfma_rate.argtypes = [C.c_void_p, C.POINTER(C.c_double)]
         lib.bb_gemm_static.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p]
         _LIB = lib
@@ -155,6 +156,8 @@ class StepView:
         return self._bb._read(self._raw.lse_dev, self.m_lm, np.float32)
 
     def logits(self):
+        if not self._raw.logits_dev:
+            raise BBError("the logits were not stored: call keep_logits() before the forward")
         v = self._bb.model.vocab
         return self._bb._read(self._raw.logits_dev, self.m_lm * v, np.float32).reshape(self.m_lm, v)
 
@@ -340,6 +343,10 @@ class BlockBatch:
         nbytes = src.numel() * src.element_size()
         assert nbytes == dst.numel() * dst.element_size()
         self._chk(self.lib.bb_debug_copy16(self._ctx, C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), nbytes), "bb_debug_copy16")
+
+    def keep_logits(self, on=True):
+        """Tests: make the forwards store the fp32 logits too (StepView.logits needs it)."""
+        self._chk(self.lib.bb_debug_keep_logits(self._ctx, int(on)), "bb_debug_keep_logits")
 
     def debug_mfma_rate(self):
         """TFLOP/s of a pure 32x32x16 bf16 MFMA loop on this chip (measured peak)."""

@@ -39,6 +39,7 @@ struct bb_ctx {
     char* d_stats;                      // device staging for stats copies
     std::string err;
     int last_forward_rows, last_lm_cap;
+    int keep_logits;                    // tests: the LM head also stores its fp32 logits (bb_debug_keep_logits)
     // per-launch event timing (bb_profile_*)
     int prof_on;
     struct ProfRec { hipEvent_t a, b; int klass; double bytes, flops; bool own_a; };
@@ -154,7 +155,8 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.seg_off = b.take<int>(nbr); D.seg_rows = b.take<int>(nbr);
     D.lm_row = b.take<int>(lm_pad);
     D.out_pred = b.take<int>(lm_pad); D.out_conf = b.take<float>(lm_pad); D.out_lse = b.take<float>(lm_pad);
-    D.vr_part = b.take<float4>((size_t)lm_pad * 8);
+    D.vr_tiles = (m.vocab / 32 + (m.vocab / 32 >= 8 ? 7 : 3)) / (m.vocab / 32 >= 8 ? 8 : 4);   // column tiles of the LM-head GEMM (256 or 128 columns)
+    D.vr_part = b.take<float4>((size_t)lm_pad * D.vr_tiles);
     D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
     D.req_list = b.take<int>(l.max_requests);
     D.req_flags = b.take<int>(l.max_requests);
@@ -425,7 +427,8 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         if (c->force_split[kind] > 0 && kind != 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
         const bool fused = swiglu_out && p.split_k == 1 && p.nt == 2;
         PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-        launch_gemm(W, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr);
+        GemmEpilogue epi; epi.swiglu_out = fused ? swiglu_out : nullptr;
+        launch_gemm(W, A, P, mtt, N, K, p, s, epi);
         return fused ? 0 : p.split_k;
     };
     c->prof_chain = false;              // the first launch records its own start
@@ -452,8 +455,13 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         const int mt_lm = (lm_cap + 31) / 32;
         { PROF(BB_K_GLUE, 0, 0);
           launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, c->g_final, c->Apk, mt_lm, 1, mode == 1, s); }
-        gemm(0, c->lm, c->Apk, c->logits, m.vocab, d, lm_cap, mt_lm, lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE);
-        { PROF(BB_K_GLUE, 0, 0); launch_vocab_reduce(D, c->logits, lm_cap, mode == 1, s); }
+        {   // LM head with the vocabulary reduction in its epilogue: no k split, 256-column tiles (128 for tiny vocabularies)
+            GemmPlan p = gemm_plan(lm_cap, m.vocab, d, 1, m.vocab / 32 >= 8 ? 2 : 1);
+            GemmEpilogue epi; epi.vocab_part = D.vr_part; epi.mask_id = m.mask_id; epi.keep_logits = c->keep_logits;
+            PROF(lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE, 2.0 * m.vocab * d, 2.0 * lm_cap * (double)m.vocab * d);
+            launch_gemm(c->lm, c->Apk, c->logits, mt_lm, m.vocab, d, p, s, epi);
+        }
+        { PROF(BB_K_GLUE, 0, 0); launch_vocab_finish(D, lm_cap, mode == 1, s); }
     }
     c->prof_chain = false;
     c->last_forward_rows = rows_cap; c->last_lm_cap = lm_cap;
@@ -501,7 +509,7 @@ static int bb_refresh_impl(bb_ctx* c, const int* ids, int n, int mode) {
 static void fill_view(bb_ctx* c, bb_step_view* v) {
     const Dev& D = c->D;
     v->counts_dev = D.counts; v->row_branch_dev = D.row_gbr; v->row_pos_dev = D.row_pos; v->lm_row_dev = D.lm_row;
-    v->argmax_dev = D.out_pred; v->conf_dev = D.out_conf; v->lse_dev = D.out_lse; v->logits_dev = c->logits;
+    v->argmax_dev = D.out_pred; v->conf_dev = D.out_conf; v->lse_dev = D.out_lse; v->logits_dev = c->keep_logits ? c->logits : nullptr;
     v->rows_capacity = D.lm_cap;
 }
 
@@ -607,6 +615,12 @@ static int check_one(bb_ctx* c, int id) {
 static int bb_debug_set_gemm_plan_impl(bb_ctx* c, int kind, int nt, int split_k) {
     if (!c || kind < 0 || kind > 3 || nt < 0 || nt > 2 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     c->force_nt[kind] = nt; c->force_split[kind] = split_k;
+    return BB_OK;
+}
+
+static int bb_debug_keep_logits_impl(bb_ctx* c, int on) {
+    if (!c) return BB_EINVAL;
+    c->keep_logits = on != 0;
     return BB_OK;
 }
 
@@ -961,4 +975,8 @@ extern "C" int bb_debug_mfma_rate(bb_ctx* c, double* tflops_out_host) {
 extern "C" int bb_create(bb_ctx** out, const bb_model_cfg* model, const bb_decode_cfg* decode, const bb_limits* limits,
                          void* workspace_dev, size_t workspace_bytes, void* hip_stream) {
     BB_GUARD(nullptr, bb_create_impl(out, model, decode, limits, workspace_dev, workspace_bytes, hip_stream));
+}
+
+extern "C" int bb_debug_keep_logits(bb_ctx* c, int on) {
+    BB_GUARD(c, bb_debug_keep_logits_impl(c, on));
 }

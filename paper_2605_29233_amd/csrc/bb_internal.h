@@ -57,7 +57,8 @@ struct Dev {
     int* seg_off; int* seg_rows;    // [max_req*max_br] packed rows of each branch (0 = inactive)
     int* lm_row;                // [lm_cap]
     int* out_pred; float* out_conf; float* out_lse;   // [lm_cap]
-    float4* vr_part;            // [lm_cap][8] per-segment (max, sum, argmax) of the vocabulary reduction
+    float4* vr_part;            // [lm_cap][vr_tiles] per-column-tile (max, sum, argmax) of the vocabulary reduction
+    int vr_tiles;               // column tiles of the LM-head GEMM = partial results per row
     PageCopy* copies;           // [max_req*max_br*n_pages]
     int* req_list;              // [max_req] request slots of the current call
     int* req_flags;             // [max_req] per listed request after a commit: bit 0 finished, bit 1 refresh due; bits 8.. forwards until a refresh is due
@@ -113,11 +114,28 @@ static inline __host__ __device__ float bf16_to_f32(uint16_t b) {
     union { float f; uint32_t u; } v; v.u = ((uint32_t)b) << 16; return v.f;
 }
 
+// ---- running (max, rescaled sum of exponentials, argmax) of a row of logits ------------------------------
+// c = max_v softmax(l)_v = 1 / sum_v exp(l_v - max) needs only these three; ties go to the lowest token id.
+struct MSI { float m, s; int i; };
+static __device__ __forceinline__ MSI msi_merge(MSI a, MSI b) {
+    MSI r;
+    const bool a_wins = a.m > b.m || (a.m == b.m && a.i < b.i);
+    r.m = a_wins ? a.m : b.m;
+    r.i = a_wins ? a.i : b.i;
+    const float ea = a.m == -INFINITY ? 0.f : expf(a.m - r.m), eb = b.m == -INFINITY ? 0.f : expf(b.m - r.m);
+    r.s = a.s * ea + b.s * eb;
+    return r;
+}
+
 // ---- kernel launchers (each enqueues on `s`) -----------------------------------------------------
 struct GemmPlan { int split_k; int chunks_per_split; int nt; };
 GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt);
+// Epilogue of launch_gemm: partial tiles P[split][m][n] (default); SiLU(gate) * up as the down projection's panel
+// (swiglu_out, needs nt == 2 and no k split); or the vocabulary reduction of the LM head (vocab_part: per row and
+// column tile one (max, sum, argmax); needs no k split and nt <= 2; P is then written only if keep_logits).
+struct GemmEpilogue { u32x4* swiglu_out = nullptr; float4* vocab_part = nullptr; int mask_id = -1; int keep_logits = 1; };
 void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s,
-                 u32x4* swiglu_out = nullptr);
+                 GemmEpilogue epi = GemmEpilogue());
 void launch_tile_weights(const uint16_t* src, int rows, int K, u32x4* dst, int dst_row0, int interleave, hipStream_t s);
 void launch_pack_rows(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);
 
@@ -133,7 +151,7 @@ void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t
                             int rows_cap, int mt_total, hipStream_t s);
 void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int mt_total, int max_seg_rows,
                       int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, hipStream_t s);
-void launch_vocab_reduce(const Dev& D, const float* logits, int lm_cap, int bcast, hipStream_t s);
+void launch_vocab_finish(const Dev& D, int lm_cap, int bcast, hipStream_t s);
 
 void launch_pack_step(const Dev& D, int n_req, hipStream_t s);
 void launch_pack_refresh(const Dev& D, int n_req, int mode, hipStream_t s);

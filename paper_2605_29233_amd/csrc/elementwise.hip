@@ -1,6 +1,6 @@
 // Memory-bound glue kernels of the forward: embedding gather, the consumers of the GEMMs'
 // split-K partial results (residual add + RMSNorm + packing into MFMA fragments, bias + RoPE +
-// KV-cache write, SwiGLU), and the online-softmax vocabulary reduction.
+// KV-cache write, SwiGLU), and the second half of the vocabulary reduction.
 #include "bb_internal.h"
 
 static __device__ __forceinline__ float wg_sum(float v, float* sh) {
@@ -399,65 +399,28 @@ void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t
     swiglu_epilogue_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(D, gu, n_partial, partial_stride, ldp, Apk, mt_total);
 }
 
-// Top-1 confidence c = max_v softmax(l)_v = 1 / sum_v exp(l_v - max) and its token, in one
-// pass over the row with a running (max, rescaled sum, index); the mask token is skipped and
-// ties go to the lowest token id.  Probabilities are never written out.
-struct MSI { float m, s; int i; };
-static __device__ __forceinline__ MSI msi_merge(MSI a, MSI b) {
-    MSI r;
-    const bool a_wins = a.m > b.m || (a.m == b.m && a.i < b.i);
-    r.m = a_wins ? a.m : b.m;
-    r.i = a_wins ? a.i : b.i;
-    const float ea = a.m == -INFINITY ? 0.f : expf(a.m - r.m), eb = b.m == -INFINITY ? 0.f : expf(b.m - r.m);
-    r.s = a.s * ea + b.s * eb;
-    return r;
-}
-
-// Pass 1: workgroup (row j, segment) reduces its share of the row to (max, rescaled sum, argmax).
-#define VOCAB_SEGS 8
-__global__ __launch_bounds__(256) void vocab_reduce_kernel(Dev D, const float* __restrict__ logits) {
-    __shared__ MSI sh[4];
-    const int j = blockIdx.x, seg = blockIdx.y;
+// Second half of the vocabulary reduction.  The LM-head GEMM leaves one (max, rescaled sum of exponentials,
+// argmax) per row and column tile (its epilogue reduces the logits in registers: they are not read back, and not
+// even written unless a test asks for them); here one wave per row merges the column tiles: each lane its tiles in
+// ascending order, then the lanes pairwise.  The merge is symmetric, so every row sees the same tree wherever it
+// sits.  Top-1 confidence c = max_v softmax(l)_v = 1 / sum_v exp(l_v - max); probabilities are never formed.
+// Writes confidence, token and lse, also into the probability map of the row's branch (of every branch of the
+// request after the initial forward).
+__global__ __launch_bounds__(256) void vocab_finish_kernel(Dev D, int bcast) {
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
     if (j >= D.counts[1]) return;
-    const float4* row = reinterpret_cast<const float4*>(logits + (size_t)j * D.vocab);
-    const int n4 = D.vocab >> 2, per = (n4 + VOCAB_SEGS - 1) / VOCAB_SEGS, lo = seg * per, hi = min(n4, lo + per);
-    MSI a = {-INFINITY, 0.f, 0x7fffffff};
-    for (int v4 = lo + threadIdx.x; v4 < hi; v4 += blockDim.x) {
-        const float4 x4 = row[v4];
-        const float xs[4] = {x4.x, x4.y, x4.z, x4.w};
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int v = v4 * 4 + q;
-            const float x = xs[q];
-            if (v == D.mask_id) continue;
-            if (x > a.m) { a.s = a.s * expf(a.m - x) + 1.f; a.m = x; a.i = v; }
-            else a.s += expf(x - a.m);
-        }
+    const float4* row = D.vr_part + (size_t)j * D.vr_tiles;
+    MSI t = {-INFINITY, 0.f, 0x7fffffff};
+    for (int b = lane; b < D.vr_tiles; b += 64) {
+        const float4 p = row[b];
+        const MSI o = {p.x, p.y, __float_as_int(p.z)};
+        t = msi_merge(t, o);
     }
     for (int o = 32; o > 0; o >>= 1) {
-        MSI b = {__shfl_xor(a.m, o, 64), __shfl_xor(a.s, o, 64), __shfl_xor(a.i, o, 64)};
-        a = msi_merge(a, b);
+        const MSI b = {__shfl_xor(t.m, o, 64), __shfl_xor(t.s, o, 64), __shfl_xor(t.i, o, 64)};
+        t = (lane & o) ? msi_merge(b, t) : msi_merge(t, b);      // both partners form the same merge
     }
-    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = a;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        MSI t = sh[0];
-        for (int w = 1; w < 4; ++w) t = msi_merge(t, sh[w]);
-        D.vr_part[(size_t)j * VOCAB_SEGS + seg] = make_float4(t.m, t.s, __int_as_float(t.i), 0.f);
-    }
-}
-
-// Pass 2: one thread per row merges the segments in order and writes confidence, token and lse, also into the
-// probability map of the row's branch (of every branch of the request after the initial forward).
-__global__ void vocab_finish_kernel(Dev D, int bcast) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= D.counts[1]) return;
-    MSI t = {-INFINITY, 0.f, 0x7fffffff};
-    for (int seg = 0; seg < VOCAB_SEGS; ++seg) {
-        const float4 p = D.vr_part[(size_t)j * VOCAB_SEGS + seg];
-        const MSI b = {p.x, p.y, __float_as_int(p.z)};
-        t = msi_merge(t, b);
-    }
+    if (lane != 0) return;
     const float conf = 1.0f / t.s, lse = t.m + logf(t.s);
     D.out_pred[j] = t.i; D.out_conf[j] = conf; D.out_lse[j] = lse;
     const int r = D.lm_row[j];
@@ -471,7 +434,6 @@ __global__ void vocab_finish_kernel(Dev D, int bcast) {
     }
 }
 
-void launch_vocab_reduce(const Dev& D, const float* logits, int lm_cap, int bcast, hipStream_t s) {
-    vocab_reduce_kernel<<<dim3(lm_cap, VOCAB_SEGS), 256, 0, s>>>(D, logits);
-    vocab_finish_kernel<<<(lm_cap + 63) / 64, 64, 0, s>>>(D, bcast);
+void launch_vocab_finish(const Dev& D, int lm_cap, int bcast, hipStream_t s) {
+    vocab_finish_kernel<<<(lm_cap + 3) / 4, 256, 0, s>>>(D, bcast);
 }

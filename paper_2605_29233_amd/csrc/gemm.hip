@@ -50,11 +50,20 @@ static __device__ __forceinline__ bf16x8 as_bf16x8(const u32x4& v) {
 // SWIGLU: the weight matrix is the fused gate/up projection (32 gate rows alternate with the 32 up rows of
 // the same features, so a wave's two tiles are gate and up of one feature group); instead of P the
 // kernel writes act = SiLU(gate) * up as the packed hi/lo panel Opk of the down projection (no k split).
-template <int NT, bool SWIGLU>
+#define EPI_PARTIAL 0
+#define EPI_SWIGLU 1
+#define EPI_VOCAB 2
+// EPI_VOCAB: the weight matrix is the LM head; per tile every row's logits are reduced to (max, rescaled sum of
+// exponentials, argmax) over the tile's columns (the mask token and padded columns excluded) and written to
+// Vp[row][column tile]; a second kernel merges the column tiles of a row in a fixed order.  The logits themselves
+// are stored only when keep_logits is set (tests).
+template <int NT, int EPI>
 __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ Wt, const u32x4* __restrict__ Apk,
                                                       float* __restrict__ P, size_t split_stride, int ldp, int mt_total,
                                                       int n_tiles, int ksteps, int chunks_per_split, int tiles_x, int tiles_y,
-                                                      u32x4* __restrict__ Opk) {
+                                                      u32x4* __restrict__ Opk, float4* __restrict__ Vp, int mask_id,
+                                                      int keep_logits) {
+    constexpr bool SWIGLU = EPI == EPI_SWIGLU;
     __shared__ u32x4 lds[3][CHUNK_U4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // a workgroup walks the (column group, row group) tiles with the grid's stride: at most one round of
@@ -242,6 +251,40 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
         }
         continue;
     }
+    if constexpr (EPI == EPI_VOCAB) {
+        static_assert(EPI != EPI_VOCAB || NT <= 2, "vocabulary epilogue is written for one or two tiles per wave");
+        // Lane l holds, for activation row l % 32 of every m-tile, 16 columns of each of its weight tiles, in
+        // ascending column order (register r <-> column 8 (r/4) + 4 (l/32) + r%4): a strict '>' keeps the lowest id.
+        __shared__ MSI sV[4][MT * 32];
+        const int x0v = (bx * 4 + wave) * NT, gv = lane >> 5;
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            MSI a = {-INFINITY, 0.f, 0x7fffffff};
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                if (x0v + t >= n_tiles) break;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int v = (x0v + t) * 32 + 8 * (r >> 2) + 4 * gv + (r & 3);
+                    const float x = acc[t][mt][r];
+                    if (v == mask_id) continue;
+                    if (x > a.m) { a.s = a.s * expf(a.m - x) + 1.f; a.m = x; a.i = v; }
+                    else a.s += expf(x - a.m);
+                }
+            }
+            const MSI b = {__shfl_xor(a.m, 32, 64), __shfl_xor(a.s, 32, 64), __shfl_xor(a.i, 32, 64)};
+            a = gv == 0 ? msi_merge(a, b) : msi_merge(b, a);       // both halves compute the same merge
+            if (gv == 0) sV[wave][mt * 32 + (lane & 31)] = a;
+        }
+        __syncthreads();
+        if (threadIdx.x < mt_cnt * 32) {
+            MSI t4 = sV[0][threadIdx.x];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) t4 = msi_merge(t4, sV[w][threadIdx.x]);
+            Vp[(size_t)(mt0 * 32 + threadIdx.x) * tiles_x + bx] = make_float4(t4.m, t4.s, __int_as_float(t4.i), 0.f);
+        }
+        if (!keep_logits) { __syncthreads(); continue; }
+    }
     // C^T accumulator layout of the 32x32 MFMA: register r of lane l holds
     //   weight row n = 8*(r/4) + 4*(l/32) + r%4 of the tile, activation row m = l%32.
     // The tile goes through LDS (each wave its own slice, one or two m-tiles at a time) so that the global
@@ -318,21 +361,26 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
     return p;
 }
 
-// Opk != nullptr: fused gate/up projection with the SwiGLU epilogue (needs plan.nt == 2 and plan.split_k == 1).
 void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s,
-                 u32x4* Opk) {
+                 GemmEpilogue epi) {
     const int n_tiles = N / 32, ksteps = (K + 63) / 64 * 4, m_groups = (mt_total + MT - 1) / MT;     // K padded to whole chunks
     const size_t split_stride = (size_t)mt_total * 32 * N;
     const int tiles_x = (n_tiles + 4 * plan.nt - 1) / (4 * plan.nt);
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
-    if (Opk)
-        gemm_kernel<2, true><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, Opk);
+#define GEMM_ARGS Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, epi.swiglu_out, epi.vocab_part, epi.mask_id, epi.keep_logits
+    if (epi.swiglu_out)
+        gemm_kernel<2, EPI_SWIGLU><<<grid, 256, 0, s>>>(GEMM_ARGS);
+    else if (epi.vocab_part && plan.nt == 2)
+        gemm_kernel<2, EPI_VOCAB><<<grid, 256, 0, s>>>(GEMM_ARGS);
+    else if (epi.vocab_part)
+        gemm_kernel<1, EPI_VOCAB><<<grid, 256, 0, s>>>(GEMM_ARGS);
     else if (plan.nt == 3)
-        gemm_kernel<3, false><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, nullptr);
+        gemm_kernel<3, EPI_PARTIAL><<<grid, 256, 0, s>>>(GEMM_ARGS);
     else if (plan.nt == 2)
-        gemm_kernel<2, false><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, nullptr);
+        gemm_kernel<2, EPI_PARTIAL><<<grid, 256, 0, s>>>(GEMM_ARGS);
     else
-        gemm_kernel<1, false><<<grid, 256, 0, s>>>(Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, nullptr);
+        gemm_kernel<1, EPI_PARTIAL><<<grid, 256, 0, s>>>(GEMM_ARGS);
+#undef GEMM_ARGS
 }
 
 // The destination is laid out for K padded to a multiple of 64 (whole chunks); the padding must be zero.

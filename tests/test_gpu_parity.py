@@ -102,6 +102,28 @@ def test_head_dim_128_small():
     check_report(s)
 
 
+def test_tiny_full_trajectory_without_stored_logits():
+    """The production configuration: the LM head reduces each row's logits to (max, sum, argmax) in its epilogue and
+    stores none.  Confidence, log-sum-exp, argmax and every commit / merge / sync decision are compared as always."""
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 0))
+    om = OracleModel(w.model, weights, np.float64)
+    bb = make_bb(w.model, w.decode, weights, 3, 128, 64, sum(w.block_sizes))
+    try:
+        bb.keep_logits(False)
+        s = SideBySide(bb, om, gen_prompt(w.model, 0, 0, 64), 64, w.block_sizes, w.decode, conf_tol=5e-4)
+        s.compare_logits = False
+        s.run()
+        with pytest.raises(Exception):
+            bb.denoise_step([s.rid]).logits()
+        s.final = bb.get_stats(s.rid)
+        print("parity without logits:", s.rep, flush=True)
+        assert s.o.all_done() and s.rep.max_conf_err <= 5e-4 and s.rep.merges > 0
+        check_report(s)
+    finally:
+        bb.close()
+
+
 def test_last_page_holds_one_key():
     """L = 2 * 64 + 1: the third cache page of every row holds a single key."""
     w = workload("tiny")
