@@ -88,6 +88,24 @@ def test_tiny_variants(seed, blocks, prompt_len, gen_len, decode):
     check_report(s)
 
 
+@pytest.mark.parametrize("seed", range(100, 124))
+def test_random_configurations(seed):
+    """Seeded draws of model shape (MHA head 64, GQA with bias, head 128), block-size set, decode parameters
+    (thresholds, tau_sync, R, leader rule, an EOS id), prompt and generation length; up to 30 steps each."""
+    w = workload("tiny")
+    shapes = [w.model, ModelShape("tiny_gqa", 2, 256, 4, 2, 64, 688, 1024, qkv_bias=True, lm_std=0.5),
+              ModelShape("small128", 2, 512, 4, 2, 128, 1024, 2048, lm_std=0.35)]
+    blocksets = [(8, 16, 32), (4, 8, 32), (2, 4, 8, 16), (16, 16), (32,), (1, 3, 5, 7), (8, 64), (4, 8, 16, 32, 64)]
+    decs = [DecodeParams(0.9, 0.5, 8, 4, 0), DecodeParams(0.9, 0.5, 2, 3, 0), DecodeParams(0.7, 0.3, 4, 5, 1),
+            DecodeParams(0.95, 0.6, 1, 2, 0), DecodeParams(0.9, 0.5, 8, 4, 0, eos_id=17)]
+    rng = np.random.default_rng(seed)
+    shape, blocks, dec = shapes[seed % 3], blocksets[rng.integers(len(blocksets))], decs[rng.integers(len(decs))]
+    lp, g = int(rng.integers(20, 150)), int(rng.choice([40, 64, 72, 100]))
+    s = run_case(shape, dec, lp, g, blocks, seed=seed, max_steps=30, kv=(seed % 4 == 0))
+    assert s.rep.max_logit_err <= 3e-2 and s.rep.asserted_steps == s.rep.commit_steps, s.rep
+    assert (s.final.finished, s.final.winner if s.final.finished else -1) == (s.o.finished, s.o.winner if s.o.finished else -1)
+
+
 def test_tiny_gqa_with_bias():
     shape = ModelShape("tiny_gqa", 2, 256, 4, 2, 64, 688, 1024, qkv_bias=True, lm_std=0.5)
     s = run_case(shape, DecodeParams(0.9, 0.5, 4, 4, 0), 50, 64, (8, 16, 32), seed=7, max_steps=20)
