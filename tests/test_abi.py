@@ -75,3 +75,17 @@ def test_bad_shapes_are_rejected(lib):
     assert lib.bb_create(C.byref(ctx), C.byref(mc), None, C.byref(lim), None, 0, None) == -1
     assert lib.bb_destroy(None) == -1
     assert lib.bb_last_error(None) == b"null context"
+
+
+def test_static_gemm_rejects_bad_sizes_before_touching_a_device(lib):
+    """Argument and limit checks of the entry point that allocates nothing run on the host alone."""
+    fake = C.c_void_p(4096)                      # never dereferenced: every call below is refused first
+    f = lib.bb_gemm_static
+    assert f(None, fake, fake, 8, 64, 64, 0, None) == -1
+    assert f(fake, fake, fake, 0, 64, 64, 0, None) == -1          # no rows
+    assert f(fake, fake, fake, 8, 48, 64, 0, None) == -1          # N not a multiple of 32
+    assert f(fake, fake, fake, 8, 64, 24, 0, None) == -1          # K not a multiple of 16
+    assert f(fake, fake, fake, 129, 64, 64, 0, None) == -3        # beyond the row limit
+    assert f(fake, fake, fake, 8, 4128, 64, 0, None) == -3        # beyond the column limit
+    assert f(fake, fake, fake, 8, 2048, 4096, 0, None) == -3      # N * K beyond 4 Mi
+    assert f(fake, fake, fake, 8, 64, 64, 5, None) == -3          # k split beyond 4
