@@ -48,23 +48,9 @@ void launch_embed(const Dev& D, const uint16_t* emb, float* h, int rows_cap, hip
     embed_kernel<<<rows_cap, 256, 0, s>>>(D, emb, h);
 }
 
-// Sum of split-K partial results in split order; all loads of a batch of four are issued
-// before the first add so several are in flight per thread.
-static __device__ __forceinline__ float4 part_sum4(const float* __restrict__ P, int n_split, size_t stride, size_t off) {
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < n_split; s += 4) {
-        float4 p[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            p[u] = s + u < n_split ? *reinterpret_cast<const float4*>(&P[(s + u) * stride + off]) : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { v.x += p[u].x; v.y += p[u].y; v.z += p[u].z; v.w += p[u].w; }
-    }
-    return v;
-}
-
-// The same for N offsets at once: the loads of a batch (4 splits x N offsets) are all issued before the
-// first add, so a thread pays the memory latency once per batch and not once per offset.
+// Sum of split-K partial results in split order, for N offsets at once: the loads of a batch (4 splits x N
+// offsets) are all issued before the first add, so a thread pays the memory latency once per batch and not
+// once per offset.
 template <int N>
 static __device__ __forceinline__ void part_sum4n(const float* __restrict__ P, int n_split, size_t stride, const size_t (&off)[N],
                                                   float4 (&out)[N]) {

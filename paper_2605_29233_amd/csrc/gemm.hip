@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
             if (gv == 0) sV[wave][mt * 32 + (lane & 31)] = a;
         }
         __syncthreads();
-        if (threadIdx.x < mt_cnt * 32) {
+        if ((int)threadIdx.x < mt_cnt * 32) {
             MSI t4 = sV[0][threadIdx.x];
 #pragma unroll
             for (int w = 1; w < 4; ++w) t4 = msi_merge(t4, sV[w][threadIdx.x]);
