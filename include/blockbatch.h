@@ -253,7 +253,7 @@ int bb_gemm_static(const float* A_dev, const uint16_t* W_dev, float* C_dev, int 
  * logits_dev); off (the default) the logits exist only in the registers of the LM-head GEMM. */
 int bb_debug_keep_logits(bb_ctx* ctx, int on);
 
-/* Tuning knob: override the tile width (nt = 1: 128 columns, 2: 256; 0 = heuristic) and the
+/* Tuning knob: override the tile width (nt = 1: 128 columns, 2: 256, 3: 384; 0 = heuristic) and the
  * split-K factor (0 = heuristic) of one GEMM kind (1 O/down, 2 gate/up, 3 QKV; 0, the LM head, is fixed) for
  * panels of at most 128 rows.  Results are unchanged up to fp32 summation order. */
 int bb_debug_set_gemm_plan(bb_ctx* ctx, int kind, int nt, int split_k);

@@ -613,7 +613,7 @@ static int check_one(bb_ctx* c, int id) {
 }
 
 static int bb_debug_set_gemm_plan_impl(bb_ctx* c, int kind, int nt, int split_k) {
-    if (!c || kind < 0 || kind > 3 || nt < 0 || nt > 2 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
+    if (!c || kind < 0 || kind > 3 || nt < 0 || nt > 3 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     c->force_nt[kind] = nt; c->force_split[kind] = split_k;
     return BB_OK;
 }

@@ -1,5 +1,6 @@
 """Kernel-level GPU checks through the C ABI: the MFMA GEMM path (tile edges, split-K, K = 688)
-and the bit-equality of the input generator on the two devices."""
+the q|k|v projection under every tile width and k split, and the bit-equality of the input generator on the
+two devices."""
 import numpy as np
 import pytest
 import torch
@@ -44,3 +45,46 @@ def test_mfma_gemm_matches_fp64(bb, M, N, K, split):
     err = np.abs(C - ref).max()
     # hi+lo bf16 keeps >= 16 bits of each activation; fp32 accumulation over K terms
     assert err <= 2e-5 * scale * max(1.0, (K / 256) ** 0.5), (err, scale)
+
+
+@pytest.mark.parametrize("hq,hkv,hd,bias", [(4, 2, 64, True), (2, 1, 128, False), (6, 2, 64, True)])
+def test_qkv_projection_gives_the_same_cache_and_logits_under_every_plan(hq, hkv, hd, bias):
+    """The q|k|v projection of the block forward with tiles of 128, 256 or 384 columns and with k whole or split in
+    two (partial tiles summed by the epilogue kernel that applies bias and RoPE and writes q and the K,V cache):
+    every plan must give the same cache and logits up to fp32 summation order, for block sizes with and without
+    whole runs of 8 rows, with grouped heads of 64 and 128 dims."""
+    from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT
+    from workload.gen import gen_weights, gen_prompt
+    shape = ModelShape("qkvtest", 2, 512, hq, hkv, hd, 512, 1024, qkv_bias=bias)
+    decode = DecodeParams(0.9, 0.5, 4, 8)
+    weights = dict(gen_weights(shape, 3))
+    prompt = gen_prompt(shape, 3, 0, 37)
+    G, blocks = 48, (4, 8, 16)
+    results = {}
+    for nt, split in [(1, 2), (1, 1), (2, 1), (3, 1), (2, 2)]:
+        print(f"qkv plan nt={nt} split={split} heads={hq}/{hkv} hd={hd}", flush=True)
+        b = BlockBatch(shape, decode, Limits(1, 3, 37 + G, G, 32), poison_workspace=True)
+        try:
+            b.load_weights(weights.items())
+            b.keep_logits(True)
+            b.set_gemm_plan(3, nt, split)
+            rid = b.request_open(prompt, G, blocks)
+            b.refresh([rid], BB_INIT)
+            b.merge_commit([rid])
+            out = []
+            for step in range(3):
+                v = b.denoise_step([rid])
+                out.append(v.logits().copy())
+                b.merge_commit([rid])
+            kv = [b.get_kv(rid, k, layer) for k in range(3) for layer in range(2)]
+            results[(nt, split)] = (out, kv, b.get_tokens(rid))
+        finally:
+            b.close()
+    ref_out, ref_kv, ref_X = results[(1, 2)]
+    for key, (out, kv, X) in results.items():
+        assert np.array_equal(X, ref_X), key
+        for a, r in zip(out, ref_out):
+            assert a.shape == r.shape and np.abs(a - r).max() <= 2e-4, (key, np.abs(a - r).max())
+        for (K, V), (Kr, Vr) in zip(kv, ref_kv):
+            assert np.abs(K - Kr).max() <= 1e-5 * max(1.0, np.abs(Kr).max()), key
+            assert np.abs(V - Vr).max() <= 1e-5 * max(1.0, np.abs(Vr).max()), key
