@@ -203,6 +203,11 @@ int bb_set_state(bb_ctx* ctx, int req_id, const int32_t* X_host /* [N][L] */,
 /* Cache row of one branch in one layer as the attention of that branch sees it, widened to
  * fp32: K_host, V_host [L][n_kv_heads][head_dim]. */
 int bb_get_kv(bb_ctx* ctx, int req_id, int branch, int layer, float* K_host, float* V_host);
+/* Tests: overwrite the cache row of one branch in one layer with K_host, V_host [L][n_kv_heads][head_dim] (the layout
+ * bb_get_kv returns; each value is stored as two fp16 terms, |value| <= 65504 or BB_EINVAL).  Pages the branch still
+ * shares with the initial forward's row (App. D, Alg. 1: the broadcast cache) are first made private in every layer,
+ * so no other branch sees the change.  BB_ESTATE before the request's initial forward.  Synchronises the stream. */
+int bb_set_kv(bb_ctx* ctx, int req_id, int branch, int layer, const float* K_host, const float* V_host);
 /* Plain device-to-host copy after a stream synchronise (for the pointers of bb_step_view). */
 int bb_read_device(bb_ctx* ctx, const void* src_dev, void* dst_host, size_t bytes);
 int bb_synchronize(bb_ctx* ctx);

@@ -64,7 +64,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate", "bb_debug_keep_logits")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_set_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate", "bb_debug_keep_logits")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -98,6 +98,7 @@ def load_library():
         lib.bb_get_stats.argtypes = [C.c_void_p, C.c_int, C.POINTER(RequestStats)]
         lib.bb_set_state.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         lib.bb_get_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        lib.bb_set_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         lib.bb_read_device.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t]
         lib.bb_synchronize.argtypes = [C.c_void_p]
         lib.bb_debug_set_gemm_plan.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int]
@@ -336,6 +337,14 @@ class BlockBatch:
         V = np.empty(shp, dtype=np.float32)
         self._chk(self.lib.bb_get_kv(self._ctx, rid, branch, layer, K.ctypes.data_as(C.c_void_p), V.ctypes.data_as(C.c_void_p)), "bb_get_kv")
         return K, V
+
+    def set_kv(self, rid, branch, layer, K, V):
+        n, L = self._req[rid]
+        shp = (L, self.model.n_kv_heads, self.model.head_dim)
+        K = np.ascontiguousarray(K, dtype=np.float32)
+        V = np.ascontiguousarray(V, dtype=np.float32)
+        assert K.shape == shp and V.shape == shp
+        self._chk(self.lib.bb_set_kv(self._ctx, rid, branch, layer, K.ctypes.data_as(C.c_void_p), V.ctypes.data_as(C.c_void_p)), "bb_set_kv")
 
     def debug_copy16(self, src, dst):
         """Plain 16-byte-per-lane device copy of one torch tensor into another (traffic-counter reference)."""

@@ -718,6 +718,24 @@ static int bb_get_kv_impl(bb_ctx* c, int id, int branch, int layer, float* K, fl
     return BB_OK;
 }
 
+static int bb_set_kv_impl(bb_ctx* c, int id, int branch, int layer, const float* K, const float* V) {
+    if (check_one(c, id) != BB_OK || !K || !V) return BB_EINVAL;
+    const HostReq& R = c->reqs[id];
+    if (branch < 0 || branch >= R.N || layer < 0 || layer >= c->m.n_layers) return BB_EINVAL;
+    if (!R.initialised) return fail(c, BB_ESTATE, "the request has no cache yet: run bb_refresh(BB_INIT) first");
+    const size_t n = (size_t)R.L * c->m.n_kv_heads * c->m.head_dim;
+    for (size_t i = 0; i < n; ++i)
+        if (!(std::fabs(K[i]) <= 65504.f) || !(std::fabs(V[i]) <= 65504.f)) return fail(c, BB_EINVAL, "cache value outside the fp16 range");
+    float* dK = c->dbg; float* dV = c->dbg + n;
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    HIPCHK(c, hipMemcpy(dK, K, n * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, hipMemcpy(dV, V, n * 4, hipMemcpyHostToDevice));
+    launch_write_kv(c->D, id, branch, layer, dK, dV, R.L, c->stream);
+    HIPCHK(c, hipGetLastError());
+    HIPCHK(c, hipStreamSynchronize(c->stream));
+    return BB_OK;
+}
+
 static int bb_debug_gemm_impl(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
     if (!c || !A || !W || !C || M < 1 || N < 32 || K < 16 || N % 32 || K % 16 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     const int mt = (M + 31) / 32, rows_pad = mt * 32;
@@ -954,6 +972,10 @@ extern "C" int bb_set_state(bb_ctx* c, int id, const int32_t* X, const bb_branch
 
 extern "C" int bb_get_kv(bb_ctx* c, int id, int branch, int layer, float* K, float* V) {
     BB_GUARD(c, bb_get_kv_impl(c, id, branch, layer, K, V));
+}
+
+extern "C" int bb_set_kv(bb_ctx* c, int id, int branch, int layer, const float* K, const float* V) {
+    BB_GUARD(c, bb_set_kv_impl(c, id, branch, layer, K, V));
 }
 
 extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {

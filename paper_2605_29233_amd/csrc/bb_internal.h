@@ -159,6 +159,8 @@ void launch_page_copies(const Dev& D, hipStream_t s);
 void launch_commit_merge(const Dev& D, int n_req, const uint16_t* lm_head, hipStream_t s);
 void launch_read_kv(const Dev& D, int phys_table_row_slot, int branch, int layer, float* K, float* V, int L,
                     hipStream_t s);
+void launch_write_kv(const Dev& D, int phys_table_row_slot, int branch, int layer, const float* K, const float* V, int L,
+                     hipStream_t s);
 void launch_kv_sqdist(const Dev& D, int gbr_a, int gbr_b, const half_t* snapK, const half_t* snapV, int snap_rows, int b_row,
                       int n_pages_used, double* out, hipStream_t s);
 void launch_kv_snapshot(const Dev& D, int gbr, half_t* snapK, half_t* snapV, int snap_rows, int row, int n_pages_used, hipStream_t s);

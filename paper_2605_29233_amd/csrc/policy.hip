@@ -496,6 +496,43 @@ void launch_read_kv(const Dev& D, int slot, int branch, int layer, float* K, flo
     read_kv_kernel<<<1024, 256, 0, s>>>(D, slot * D.max_br + branch, layer, K, V, L);
 }
 
+// Queue a copy of every page of a branch row that still lives in another physical row (all layers) and re-point the
+// page table at the branch's own row: afterwards a write to this row changes no other branch's view.
+__global__ void own_all_pages_kernel(Dev D, int gbr, int own, int n_pages_used) {
+    if (threadIdx.x == 0) D.counts[2] = 0;
+    __syncthreads();
+    for (int p = threadIdx.x; p < n_pages_used; p += blockDim.x) {
+        int* e = &D.table[(size_t)gbr * D.n_pages + p];
+        if (*e != own) {
+            const int idx = atomicAdd(&D.counts[2], 1);
+            D.copies[idx] = PageCopy{*e, own, p, 0};
+            *e = own;
+        }
+    }
+}
+
+// Overwrite one layer of a (private) cache row with caller values, each as two fp16 terms.
+__global__ void write_kv_kernel(Dev D, int gbr, int layer, const float* __restrict__ K, const float* __restrict__ V, int L) {
+    const int krow = D.hkv * D.hd, hd = D.hd;
+    const size_t n = (size_t)L * krow;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const int pos = (int)(i / krow), e = (int)(i % krow), head = e / hd, dd = e % hd;
+        const int phys = D.table[(size_t)gbr * D.n_pages + pos / BB_PAGE], tt = pos % BB_PAGE;
+        const size_t blk = kv_block_off(D, layer, phys, pos / BB_PAGE, head);
+        const float k = K[i], v = V[i];
+        const half_t kh = (half_t)k, vh = (half_t)v;
+        D.Kc[blk + k_slot(tt, dd, 0, hd)] = kh; D.Kc[blk + k_slot(tt, dd, 1, hd)] = (half_t)(k - (float)kh);
+        D.Vt[blk + v_slot(tt, dd, 0)] = vh;     D.Vt[blk + v_slot(tt, dd, 1)] = (half_t)(v - (float)vh);
+    }
+}
+
+void launch_write_kv(const Dev& D, int slot, int branch, int layer, const float* K, const float* V, int L, hipStream_t s) {
+    const int gbr = slot * D.max_br + branch, own = slot * D.phys_per_req + branch;
+    own_all_pages_kernel<<<1, 256, 0, s>>>(D, gbr, own, (L + BB_PAGE - 1) / BB_PAGE);
+    page_copy_kernel<<<1024, 256, 0, s>>>(D);
+    write_kv_kernel<<<1024, 256, 0, s>>>(D, gbr, layer, K, V, L);
+}
+
 // ---- KV-consistency diagnostics (App. A.2) ---------------------------------------------------------
 // Squared distance between two cache rows, per (layer, page): out[(layer * n_pages + page)] = sum over the
 // page's K and V blocks of ((a_hi + a_lo) - (b_hi + b_lo))^2 in fp64.  A row is either a branch's view of

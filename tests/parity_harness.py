@@ -371,6 +371,13 @@ class SideBySide:
             n += 1
         return self.rep
 
+    def import_cache(self):
+        """Put the oracle's K,V of every branch that is still decoding into the library (bb_set_kv): after this the
+        two caches differ by the rounding to two fp16 terms only, whatever drift the earlier steps left."""
+        for br in self.o.active():
+            for layer in range(self.o.m.s.n_layers):
+                self.bb.set_kv(self.rid, br.k, layer, self.o.K[br.k][layer][:self.o.L], self.o.V[br.k][layer][:self.o.L])
+
     def compare_kv(self, branch, layer, tol_rel=2e-3):
         K, V = self.bb.get_kv(self.rid, branch, layer)
         Ko, Vo = self.o.K[branch][layer][:self.o.L], self.o.V[branch][layer][:self.o.L]

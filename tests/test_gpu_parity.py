@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 
 def run_case(model, decode, prompt_len, gen_len, blocks, seed=0, max_steps=10 ** 9, kv=True, dtype=np.float64,
-             weights_device="cpu", conf_tol=5e-4):
+             weights_device="cpu", conf_tol=5e-4, import_cache=False):
     """conf_tol: with the oracle in fp64 on these small models the confidences agree to a few 1e-5, so a
     tenth of the general bound is asserted and the pairwise guard band shrinks with it."""
     print(f"parity case {model.name} blocks={blocks} L_p={prompt_len} G={gen_len} seed={seed}", flush=True)
@@ -38,6 +38,10 @@ def run_case(model, decode, prompt_len, gen_len, blocks, seed=0, max_steps=10 **
         while not sbs.o.all_done() and n < max_steps:
             if sbs.o.refresh_due:
                 sbs.refresh()
+                if kv:
+                    check_kv(sbs)
+            if import_cache:
+                sbs.import_cache()
                 if kv:
                     check_kv(sbs)
             sbs.step()
@@ -535,5 +539,63 @@ def test_error_paths():
         assert view.m_q == 0 and view.m_lm == 0
         st2 = bb.merge_commit([r2])[0]
         assert st2.finished == 1 and st2.winner == st.winner and np.array_equal(bb.get_tokens(r2), X)
+    finally:
+        bb.close()
+
+
+def test_tiny_trajectory_with_the_cache_reset_to_the_oracle_before_every_step():
+    """Teacher forcing of the cache as well: before every block forward bb_set_kv overwrites each active branch row
+    with the oracle's K,V, so no difference can build up over the trajectory (between refreshes a finished block's
+    K,V stay as last computed, App. A.1).  The whole protocol must hold as without the import, and the logits must
+    agree as closely as in a first step: the remaining difference is one forward's rounding."""
+    w = workload("tiny")
+    s = run_case(w.model, w.decode, 64, 64, (8, 16, 32), import_cache=True)
+    check_report(s)
+    assert s.rep.max_logit_err <= 1e-3, s.rep
+
+
+def test_set_kv_round_trip_isolation_and_errors():
+    """bb_set_kv then bb_get_kv returns the values (exactly, when they are sums of two fp16 terms, as everything
+    bb_get_kv returns is); a branch written right after the initial forward, while all rows still share the
+    broadcast cache, leaves the other branches' rows and its own other layers as they were; bad calls are refused."""
+    from paper_2605_29233_amd import BB_INIT
+    from paper_2605_29233_amd.binding import BBError
+    w = workload("tiny")
+    weights = dict(gen_weights(w.model, 2))
+    prompt = gen_prompt(w.model, 2, 0, 70)                   # L = 70 + 59 = 129: the last page holds one token
+    bb = make_bb(w.model, w.decode, weights, 3, 129, 59, 8 + 16 + 32)
+    try:
+        rid = bb.request_open(prompt, 59, (8, 16, 32))
+        shp = (129, w.model.n_kv_heads, w.model.head_dim)
+        with pytest.raises(BBError, match="BB_ESTATE"):
+            bb.set_kv(rid, 0, 0, np.zeros(shp, np.float32), np.zeros(shp, np.float32))
+        bb.refresh([rid], BB_INIT)
+        before = {(k, l): bb.get_kv(rid, k, l) for k in range(3) for l in range(w.model.n_layers)}
+        rng = np.random.default_rng(0)
+        K1 = before[(1, 1)][0][::-1].copy()                  # stored values, moved and negated, are still sums of two fp16 terms
+        V1 = -before[(1, 1)][1][::-1]
+        bb.set_kv(rid, 1, 1, K1, V1)
+        for (k, l), (K0, V0) in before.items():
+            K, V = bb.get_kv(rid, k, l)
+            if (k, l) == (1, 1):
+                assert np.array_equal(K, K1) and np.array_equal(V, V1)
+            else:
+                assert np.array_equal(K, K0) and np.array_equal(V, V0), (k, l)
+        # arbitrary fp32 values come back to two-fp16-term accuracy (2^-22 relative)
+        Kr = rng.standard_normal(shp).astype(np.float32)
+        Vr = rng.standard_normal(shp).astype(np.float32)
+        bb.set_kv(rid, 2, 0, Kr, Vr)
+        K, V = bb.get_kv(rid, 2, 0)
+        assert np.abs(K - Kr).max() <= 2.0 ** -19 and np.abs(V - Vr).max() <= 2.0 ** -19
+        # the library goes on from the imported row: a step runs and the written branch's own window is recomputed
+        bb.merge_commit([rid])
+        bb.denoise_step([rid])
+        K, V = bb.get_kv(rid, 0, 1)
+        assert np.array_equal(K[:70], before[(0, 1)][0][:70])          # branch 0's prompt part: untouched by its block step
+        bad = Kr.copy(); bad[3, 0, 0] = np.inf
+        with pytest.raises(BBError, match="BB_EINVAL"):
+            bb.set_kv(rid, 2, 0, bad, Vr)
+        with pytest.raises(BBError, match="BB_EINVAL"):
+            bb.set_kv(rid, 3, 0, Kr, Vr)
     finally:
         bb.close()
