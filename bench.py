@@ -53,6 +53,8 @@ def make_context(w, torch):
     step_rows = w.n_requests * sum(min(b, w.gen_len) for b in w.block_sizes)
     bb = BlockBatch(m, w.decode, Limits(w.n_requests, len(w.block_sizes), L, w.gen_len, step_rows))
     bb.load_weights(gen_weights(m, w.seed, device="cuda:0"))
+    if os.environ.get("BB_WIDE_FORMAT", "1") == "0":
+        bb.wide_format(False)
     torch.cuda.empty_cache()
     return bb, step_rows
 

@@ -236,6 +236,14 @@ int bb_profile_read(bb_ctx* ctx, bb_profile_entry* out_host, int max_entries, in
  * split_k = 0 lets the library choose. */
 int bb_debug_gemm(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, float* C_host,
                   int M, int N, int K, int split_k);
+/* The same product through the kernel that passes with many rows use: activations as fp16 + a scaled e5m2 remainder,
+ * weights as row-scaled fp16, converted to e4m3 in the kernel for the remainder's product (about 2^-16 relative
+ * accuracy per product instead of 2^-17). */
+int bb_debug_gemm_wide(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, float* C_host,
+                       int M, int N, int K, int split_k);
+/* Tests and measurements: on == 0 makes passes with more than 256 rows use two bf16 activation terms as well
+ * (the default, on != 0, is the fp16 + fp8 operand format for them). */
+int bb_debug_wide_format(bb_ctx* ctx, int on);
 
 /* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): C[M][N] = A[M][K] . W[N][K]^T through the same re-tiling,

@@ -64,7 +64,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_set_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate", "bb_debug_keep_logits")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_set_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_debug_gemm_wide", "bb_debug_wide_format", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate", "bb_debug_keep_logits")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -105,6 +105,8 @@ def load_library():
         lib.bb_profile_enable.argtypes = [C.c_void_p, C.c_int]
         lib.bb_profile_read.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(C.c_int)]
         lib.bb_debug_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
+        lib.bb_debug_gemm_wide.argtypes = lib.bb_debug_gemm.argtypes
+        lib.bb_debug_wide_format.argtypes = [C.c_void_p, C.c_int]
         lib.bb_kv_diag_scratch_bytes.restype = C.c_size_t
         lib.bb_kv_diag_scratch_bytes.argtypes = [C.c_void_p, C.c_int]
         lib.bb_kv_diagnostics.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -363,12 +365,16 @@ class BlockBatch:
         self._chk(self.lib.bb_debug_mfma_rate(self._ctx, C.byref(out)), "bb_debug_mfma_rate")
         return out.value
 
-    def debug_gemm(self, A, W_bits, split_k=0):
+    def debug_gemm(self, A, W_bits, split_k=0, wide=False):
         A = np.ascontiguousarray(A, dtype=np.float32)
         W = np.ascontiguousarray(W_bits, dtype=np.uint16)
         M, K = A.shape
         N = W.shape[0]
         out = np.empty((M, N), dtype=np.float32)
-        self._chk(self.lib.bb_debug_gemm(self._ctx, A.ctypes.data_as(C.c_void_p), W.ctypes.data_as(C.c_void_p),
-                                         out.ctypes.data_as(C.c_void_p), M, N, K, split_k), "bb_debug_gemm")
+        fn = self.lib.bb_debug_gemm_wide if wide else self.lib.bb_debug_gemm
+        self._chk(fn(self._ctx, A.ctypes.data_as(C.c_void_p), W.ctypes.data_as(C.c_void_p),
+                     out.ctypes.data_as(C.c_void_p), M, N, K, split_k), "bb_debug_gemm_wide" if wide else "bb_debug_gemm")
         return out
+
+    def wide_format(self, on=True):
+        self._chk(self.lib.bb_debug_wide_format(self._ctx, int(on)), "bb_debug_wide_format")

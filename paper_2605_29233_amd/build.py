@@ -4,7 +4,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = [os.path.join(HERE, "csrc", f) for f in ("bb_api.hip", "gemm.hip", "attention.hip", "elementwise.hip", "policy.hip", "gemm_static.hip")]
+SRC = [os.path.join(HERE, "csrc", f) for f in ("bb_api.hip", "gemm.hip", "gemm_wide.hip", "attention.hip", "elementwise.hip", "policy.hip", "gemm_static.hip")]
 LIB = os.path.join(HERE, "libblockbatch.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-value"]

@@ -81,7 +81,7 @@ static __device__ __forceinline__ void softmax_page(f32x16 (&s)[2], bool partial
 template <int HD, bool SPLITQ>
 __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* __restrict__ Q, u32x4* __restrict__ Apk,
                                                         int layer, int mt_total, int seg_base, int n_splits,
-                                                        float* __restrict__ part) {
+                                                        float* __restrict__ part, int wide) {
     constexpr int KS = HD / 16;         // k-steps of the score contraction
     constexpr int DT = HD / 32;         // 32-wide tiles of the output's head dimension
     __shared__ float sO[4][32][HD + 1];
@@ -249,21 +249,14 @@ __global__ __launch_bounds__(256, 1) void attention_kernel(Dev D, const half_t* 
         }
         const int hig = f / seg_rows, r = f % seg_rows;
         const int m = seg_off + r, k8 = ((kvh * group + hig) * HD) / 8 + d8;
-        uint16_t hi[8], lo[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            hi[e] = f32_to_bf16_rne(y[e]);
-            lo[e] = f32_to_bf16_rne(y[e] - bf16_to_f32(hi[e]));
-        }
-        Apk[packA_u4(m, k8, mt_total, 0)] = *reinterpret_cast<u32x4*>(hi);
-        Apk[packA_u4(m, k8, mt_total, 1)] = *reinterpret_cast<u32x4*>(lo);
+        store_panel8(Apk, m, k8, mt_total, y, wide);
     }
 }
 
 // Merge the splits of one tile in split order, normalise, and store the packed hi/lo panel.
 template <int HD>
 __global__ __launch_bounds__(256) void attention_combine_kernel(Dev D, const float* __restrict__ part, u32x4* __restrict__ Apk,
-                                                                int mt_total, int seg_base, int n_splits) {
+                                                                int mt_total, int seg_base, int n_splits, int wide) {
     const int gbr = seg_base + blockIdx.z;
     const int seg_rows = D.seg_rows[gbr];
     if (seg_rows == 0) return;
@@ -290,26 +283,20 @@ __global__ __launch_bounds__(256) void attention_combine_kernel(Dev D, const flo
         const float inv = 1.0f / lsum;
         const int hig = f / seg_rows, r = f % seg_rows;
         const int m = seg_off + r, k8 = ((kvh * group + hig) * HD) / 8 + d8;
-        uint16_t hi[8], lo[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float v = y[e] * inv;
-            hi[e] = f32_to_bf16_rne(v);
-            lo[e] = f32_to_bf16_rne(v - bf16_to_f32(hi[e]));
-        }
-        Apk[packA_u4(m, k8, mt_total, 0)] = *reinterpret_cast<u32x4*>(hi);
-        Apk[packA_u4(m, k8, mt_total, 1)] = *reinterpret_cast<u32x4*>(lo);
+        for (int e = 0; e < 8; ++e) y[e] *= inv;
+        store_panel8(Apk, m, k8, mt_total, y, wide);
     }
 }
 
 // max_pages: pages of the longest row among the segments; part / part_elems: scratch for split partial results.
 void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int mt_total, int max_seg_rows,
-                      int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, hipStream_t s) {
+                      int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, int wide, hipStream_t s) {
     const int group = D.hq / D.hkv, nflat = max_seg_rows * group;
     if (nflat >= 512) {     // many query rows per segment: waves take different query tiles
         dim3 grid(D.hkv, (nflat + 127) / 128, n_segs);
-        if (D.hd == 128) attention_kernel<128, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr);
-        else attention_kernel<64, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr);
+        if (D.hd == 128) attention_kernel<128, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr, wide);
+        else attention_kernel<64, true><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, 1, nullptr, wide);
         return;
     }
     // few query rows: one workgroup per tile unless that leaves most of the 256 CUs idle; then the pages of a
@@ -320,10 +307,10 @@ void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int 
     if (n_splits < 1) n_splits = 1;
     dim3 grid(D.hkv, qtiles * n_splits, n_segs), cgrid(D.hkv, qtiles, n_segs);
     if (D.hd == 128) {
-        attention_kernel<128, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, n_splits, part);
-        if (n_splits > 1) attention_combine_kernel<128><<<cgrid, 256, 0, s>>>(D, part, Apk, mt_total, seg_base, n_splits);
+        attention_kernel<128, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, n_splits, part, wide);
+        if (n_splits > 1) attention_combine_kernel<128><<<cgrid, 256, 0, s>>>(D, part, Apk, mt_total, seg_base, n_splits, wide);
     } else {
-        attention_kernel<64, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, n_splits, part);
-        if (n_splits > 1) attention_combine_kernel<64><<<cgrid, 256, 0, s>>>(D, part, Apk, mt_total, seg_base, n_splits);
+        attention_kernel<64, false><<<grid, 256, 0, s>>>(D, Q, Apk, layer, mt_total, seg_base, n_splits, part, wide);
+        if (n_splits > 1) attention_combine_kernel<64><<<cgrid, 256, 0, s>>>(D, part, Apk, mt_total, seg_base, n_splits, wide);
     }
 }

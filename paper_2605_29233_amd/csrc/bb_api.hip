@@ -12,7 +12,9 @@
 #include <vector>
 
 struct LayerW {
-    u32x4 *wqkv, *wo, *wgu, *wdown;     // tiled bf16
+    u32x4 *wqkv, *wo, *wgu, *wdown;     // tiled bf16 (passes with few rows: two bf16 activation terms)
+    u32x4 *wqkv_w, *wo_w, *wgu_w, *wdown_w;     // the same matrices as row-scaled fp16 (wide format, passes with many rows)
+    float *s_qkv, *s_o, *s_gu, *s_down; // 2^-S per weight row of the wide-format copies
     float *g_attn, *g_ffn, *bqkv;       // fp32
 };
 
@@ -28,7 +30,7 @@ struct bb_ctx {
     std::vector<char> loaded;           // per tensor slot
     int n_expected;
     // activations
-    float *h, *qkv, *part, *gu, *logits, *dbg, *attn_part;
+    float *h, *qkv, *part, *gu, *logits, *dbg, *attn_part, *wscales;
     size_t attn_part_elems;
     u32x4 *Apk, *Apk2; half_t* Q; char* stage;     // Apk2: SwiGLU output panel (written while Apk is still being read)
     size_t qkv_elems, part_elems, gu_elems, stage_bytes, dbg_bytes;
@@ -39,6 +41,7 @@ struct bb_ctx {
     char* d_stats;                      // device staging for stats copies
     std::string err;
     int last_forward_rows, last_lm_cap;
+    int wide_off;                       // tests: passes with many rows also use two bf16 terms (bb_debug_wide_format)
     int keep_logits;                    // tests: the LM head also stores its fp32 logits (bb_debug_keep_logits)
     // per-launch event timing (bb_profile_*)
     int prof_on;
@@ -87,6 +90,9 @@ struct Bump {
     }
 };
 
+// Passes over more rows than this are bound by the matrix pipes: their layer GEMMs take the wide format.
+#define BB_SKINNY_ROWS 256
+
 // Largest split-K output over every row count the forward may be called with.
 static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
     size_t best = 0;
@@ -94,6 +100,11 @@ static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
         GemmPlan p = gemm_plan(rows, N, K, 0, rows > 128 ? forced_nt_wide : 0);
         size_t e = (size_t)p.split_k * rows * N;
         if (e > best) best = e;
+        if (rows > BB_SKINNY_ROWS) {        // wide-format kernel: the plan's own tile width, or two tiles for gate/up
+            p = gemm_plan(rows, N, K, 0, forced_nt_wide);
+            e = (size_t)p.split_k * rows * N;
+            if (e > best) best = e;
+        }
     }
     // room for the largest split a tuning override may ask for on a skinny panel
     size_t tune = (size_t)BB_MAX_SPLITK * std::min((rows_cap + 31) / 32 * 32, 128) * N;
@@ -201,6 +212,21 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
         L.g_attn = b.take<float>(m.d_model); L.g_ffn = b.take<float>(m.d_model);
         L.bqkv = b.take<float>(nqkv);
     }
+    // wide-format copies (fp16, tiled like the bf16 ones) and their row scales; scales first, in one run that bb_create clears
+    auto wide_u4 = [](int N, int K) { return (size_t)N * ((K + 63) / 64 * 64) / 8; };
+    const size_t scales_per_layer = (size_t)nqkv + 2 * (size_t)m.d_model + c->ngu;
+    c->wscales = b.take<float>((size_t)m.n_layers * scales_per_layer);
+    size_t so = 0;
+    for (auto& L : c->layers) {
+        float* sp = c->wscales ? c->wscales + so : nullptr;
+        L.s_qkv = sp; L.s_o = sp ? sp + nqkv : nullptr; L.s_gu = sp ? sp + nqkv + m.d_model : nullptr;
+        L.s_down = sp ? sp + nqkv + m.d_model + c->ngu : nullptr;
+        so += scales_per_layer;
+        L.wqkv_w = b.take<u32x4>(wide_u4(nqkv, m.d_model));
+        L.wo_w = b.take<u32x4>(wide_u4(m.d_model, nq));
+        L.wgu_w = b.take<u32x4>(wide_u4(c->ngu, m.d_model));
+        L.wdown_w = b.take<u32x4>(wide_u4(m.d_model, m.d_ffn));
+    }
     (void)state_end;
     *total = align_up(b.off, 256);
 }
@@ -243,6 +269,16 @@ static int bb_create_impl(bb_ctx** out, const bb_model_cfg* model, const bb_deco
         for (auto& L : c->layers) {
             if (e == hipSuccess) e = hipMemsetAsync(L.wgu, 0, (size_t)c->ngu * model->d_model * 2, c->stream);
             if (e == hipSuccess) e = hipMemsetAsync(L.wdown, 0, (size_t)model->d_model * ((model->d_ffn + 63) / 64 * 64) * 2, c->stream);
+        }
+    // row scales of the wide-format weights: rows no tensor fills (padding of the fused gate/up matrix) must scale by 0
+    if (e == hipSuccess)
+        e = hipMemsetAsync(c->wscales, 0, sizeof(float) * model->n_layers * ((size_t)c->D.nqkv + 2 * (size_t)model->d_model + c->ngu), c->stream);
+    if (model->d_ffn % 64)
+        for (auto& L : c->layers) {
+            const size_t gu_b = (size_t)c->ngu * model->d_model * 2;
+            const size_t dn_b = (size_t)model->d_model * ((model->d_ffn + 63) / 64 * 64) * 2;
+            if (e == hipSuccess) e = hipMemsetAsync(L.wgu_w, 0, gu_b, c->stream);
+            if (e == hipSuccess) e = hipMemsetAsync(L.wdown_w, 0, dn_b, c->stream);
         }
     if (e != hipSuccess) return BB_EHIP;
     // rotary table in double precision on the host
@@ -319,17 +355,17 @@ static int load_one(bb_ctx* c, const bb_tensor& t) {
         slot = 3 + li * 12 + ki;
         switch (ki) {
             case 0: ok = t.rows * t.cols == d; if (ok) widen(L.g_attn, d); break;
-            case 1: ok = expect(nq, d); if (ok) launch_tile_weights(src, nq, d, L.wqkv, 0, 0, c->stream); break;
-            case 2: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq, 0, c->stream); break;
-            case 3: ok = expect(nkv, d); if (ok) launch_tile_weights(src, nkv, d, L.wqkv, nq + nkv, 0, c->stream); break;
+            case 1: ok = expect(nq, d); if (ok) { launch_tile_weights(src, nq, d, L.wqkv, 0, 0, c->stream); launch_tile_weights_wide(src, nq, d, L.wqkv_w, L.s_qkv, 0, 0, c->stream); } break;
+            case 2: ok = expect(nkv, d); if (ok) { launch_tile_weights(src, nkv, d, L.wqkv, nq, 0, c->stream); launch_tile_weights_wide(src, nkv, d, L.wqkv_w, L.s_qkv, nq, 0, c->stream); } break;
+            case 3: ok = expect(nkv, d); if (ok) { launch_tile_weights(src, nkv, d, L.wqkv, nq + nkv, 0, c->stream); launch_tile_weights_wide(src, nkv, d, L.wqkv_w, L.s_qkv, nq + nkv, 0, c->stream); } break;
             case 4: ok = m.qkv_bias && t.rows * t.cols == nq; if (ok) widen(L.bqkv, nq); break;
             case 5: ok = m.qkv_bias && t.rows * t.cols == nkv; if (ok) widen(L.bqkv + nq, nkv); break;
             case 6: ok = m.qkv_bias && t.rows * t.cols == nkv; if (ok) widen(L.bqkv + nq + nkv, nkv); break;
-            case 7: ok = expect(d, nq); if (ok) launch_tile_weights(src, d, nq, L.wo, 0, 0, c->stream); break;
+            case 7: ok = expect(d, nq); if (ok) { launch_tile_weights(src, d, nq, L.wo, 0, 0, c->stream); launch_tile_weights_wide(src, d, nq, L.wo_w, L.s_o, 0, 0, c->stream); } break;
             case 8: ok = t.rows * t.cols == d; if (ok) widen(L.g_ffn, d); break;
-            case 9: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 0, 1, c->stream); break;
-            case 10: ok = expect(f, d); if (ok) launch_tile_weights(src, f, d, L.wgu, 32, 1, c->stream); break;
-            case 11: ok = expect(d, f); if (ok) launch_tile_weights(src, d, f, L.wdown, 0, 0, c->stream); break;
+            case 9: ok = expect(f, d); if (ok) { launch_tile_weights(src, f, d, L.wgu, 0, 1, c->stream); launch_tile_weights_wide(src, f, d, L.wgu_w, L.s_gu, 0, 1, c->stream); } break;
+            case 10: ok = expect(f, d); if (ok) { launch_tile_weights(src, f, d, L.wgu, 32, 1, c->stream); launch_tile_weights_wide(src, f, d, L.wgu_w, L.s_gu, 32, 1, c->stream); } break;
+            case 11: ok = expect(d, f); if (ok) { launch_tile_weights(src, d, f, L.wdown, 0, 0, c->stream); launch_tile_weights_wide(src, d, f, L.wdown_w, L.s_down, 0, 0, c->stream); } break;
         }
     } else return fail(c, BB_EINVAL, "unknown tensor " + name);
     if (!ok) return fail(c, BB_EINVAL, "shape mismatch for " + name);
@@ -415,12 +451,23 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const bb_model_cfg& m = c->m; const Dev& D = c->D; hipStream_t s = c->stream;
     const int d = m.d_model, nq = m.n_q_heads * m.head_dim, f = m.d_ffn, nqkv = D.nqkv, ngu = c->ngu;
     const int mt = (rows_cap + 31) / 32, rows_pad = mt * 32;
-    const int gk = rows_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
+    const int gk = rows_cap <= BB_SKINNY_ROWS ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
+    // many rows: the layer GEMMs are bound by the matrix pipes and run in the wide format (every kernel that writes
+    // a panel for them is told so); the LM head keeps two bf16 terms (its rows are the masked ones only)
+    const int wide = rows_cap > BB_SKINNY_ROWS && !c->wide_off;
     // kind: 0 LM head, 1 O/down, 2 gate/up, 3 QKV (index of the tuning overrides)
     // swiglu_out: where the gate/up projection may put SiLU(gate) * up itself; it does when its k range
     // is not split (then 0 is returned and no partial sums exist)
-    auto gemm = [&](int kind, const u32x4* W, const u32x4* A, float* P, int N, int K, int rows, int mtt, int klass,
-                    u32x4* swiglu_out = nullptr) {
+    auto gemm = [&](int kind, const u32x4* W, const u32x4* Ww, const float* wscale, const u32x4* A, float* P, int N, int K,
+                    int rows, int mtt, int klass, u32x4* swiglu_out = nullptr) {
+        if (wide) {
+            // the fused SwiGLU epilogue pairs two tiles per wave; otherwise the plan picks the tile width
+            GemmPlan p = gemm_plan(rows, N, K, 0, swiglu_out ? 2 : 0);
+            const bool fused = swiglu_out && p.split_k == 1 && p.nt == 2;
+            PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
+            launch_gemm_wide(Ww, wscale, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr);
+            return fused ? 0 : p.split_k;
+        }
         // with many rows the gate/up projection keeps 256-column tiles: its fused SwiGLU epilogue pairs two tiles per wave
         const int nt = c->force_nt[kind] > 0 ? c->force_nt[kind] : (swiglu_out && rows > 128 ? 2 : 0);
         GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, nt);
@@ -438,23 +485,23 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const size_t pstride = (size_t)rows_pad * d;
     for (int li = 0; li < m.n_layers; ++li) {
         const LayerW& W = c->layers[li];
-        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, 0, 0, s); }
-        const int s_qkv = gemm(3, W.wqkv, c->Apk, c->qkv, nqkv, d, rows_cap, mt, gk);
+        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, 0, 0, wide, s); }
+        const int s_qkv = gemm(3, W.wqkv, W.wqkv_w, W.s_qkv, c->Apk, c->qkv, nqkv, d, rows_cap, mt, gk);
         { PROF(BB_K_GLUE, 0, 0);
           launch_qkv_epilogue(D, c->qkv, s_qkv, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s); }
         if (mode == 2 && li == m.n_layers - 1) break;
-        { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, max_pages, c->attn_part, c->attn_part_elems, s); }
-        const int s_o = gemm(1, W.wo, c->Apk, c->part, d, nq, rows_cap, mt, gk);
-        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, s); }
-        const int s_gu = gemm(2, W.wgu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, c->Apk2);
+        { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, max_pages, c->attn_part, c->attn_part_elems, wide, s); }
+        const int s_o = gemm(1, W.wo, W.wo_w, W.s_o, c->Apk, c->part, d, nq, rows_cap, mt, gk);
+        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, wide, s); }
+        const int s_gu = gemm(2, W.wgu, W.wgu_w, W.s_gu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, c->Apk2);
         if (s_gu > 0) { PROF(BB_K_GLUE, 0, 0);
-          launch_swiglu_epilogue(D, c->gu, s_gu, (size_t)rows_pad * ngu, ngu, c->Apk2, rows_cap, mt, s); }
-        s_down = gemm(1, W.wdown, c->Apk2, c->part, d, f, rows_cap, mt, gk);
+          launch_swiglu_epilogue(D, c->gu, s_gu, (size_t)rows_pad * ngu, ngu, c->Apk2, rows_cap, mt, wide, s); }
+        s_down = gemm(1, W.wdown, W.wdown_w, W.s_down, c->Apk2, c->part, d, f, rows_cap, mt, gk);
     }
     if (mode != 2) {
         const int mt_lm = (lm_cap + 31) / 32;
         { PROF(BB_K_GLUE, 0, 0);
-          launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, c->g_final, c->Apk, mt_lm, 1, mode == 1, s); }
+          launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, c->g_final, c->Apk, mt_lm, 1, mode == 1, 0, s); }
         {   // LM head with the vocabulary reduction in its epilogue: no k split, 256-column tiles (128 for tiny vocabularies)
             GemmPlan p = gemm_plan(lm_cap, m.vocab, d, 1, m.vocab / 32 >= 8 ? 2 : 1);
             GemmEpilogue epi; epi.vocab_part = D.vr_part; epi.mask_id = m.mask_id; epi.keep_logits = c->keep_logits;
@@ -736,7 +783,7 @@ static int bb_set_kv_impl(bb_ctx* c, int id, int branch, int layer, const float*
     return BB_OK;
 }
 
-static int bb_debug_gemm_impl(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
+static int bb_debug_gemm_impl(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k, int wide) {
     if (!c || !A || !W || !C || M < 1 || N < 32 || K < 16 || N % 32 || K % 16 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     const int mt = (M + 31) / 32, rows_pad = mt * 32;
     GemmPlan p = gemm_plan(M, N, K, split_k, 0);
@@ -745,17 +792,25 @@ static int bb_debug_gemm_impl(bb_ctx* c, const float* A, const uint16_t* W, floa
     float* dA = b.take<float>((size_t)M * K);
     uint16_t* dW = b.take<uint16_t>((size_t)N * K);
     const int Kp = (K + 63) / 64 * 64;
-    u32x4* dWt = b.take<u32x4>((size_t)N * Kp / 8);
+    const size_t wt_u4 = (size_t)N * Kp / 8;
+    u32x4* dWt = b.take<u32x4>(wt_u4);
     u32x4* dAp = b.take<u32x4>((size_t)rows_pad * Kp / 8 * BB_SPLIT);
+    float* dScale = b.take<float>(N);
     const size_t c_elems = (size_t)p.split_k * rows_pad * N;
     float* dC = b.take<float>(c_elems);
     if (b.off > (size_t)((char*)c->emb - (char*)c->h)) return fail(c, BB_ENOMEM, "debug gemm does not fit the activation region");
     HIPCHK(c, hipMemcpyAsync(dA, A, (size_t)M * K * 4, hipMemcpyHostToDevice, c->stream));
     HIPCHK(c, hipMemcpyAsync(dW, W, (size_t)N * K * 2, hipMemcpyHostToDevice, c->stream));
-    HIPCHK(c, hipMemsetAsync(dWt, 0, (size_t)N * Kp * 2, c->stream));
-    launch_tile_weights(dW, N, K, dWt, 0, 0, c->stream);
-    launch_pack_rows(dA, M, K, dAp, mt, c->stream);
-    launch_gemm(dWt, dAp, dC, mt, N, K, p, c->stream);
+    HIPCHK(c, hipMemsetAsync(dWt, 0, wt_u4 * sizeof(u32x4), c->stream));
+    if (wide) {
+        launch_tile_weights_wide(dW, N, K, dWt, dScale, 0, 0, c->stream);
+        launch_pack_rows_wide(dA, M, K, dAp, mt, c->stream);
+        launch_gemm_wide(dWt, dScale, dAp, dC, mt, N, K, p, c->stream);
+    } else {
+        launch_tile_weights(dW, N, K, dWt, 0, 0, c->stream);
+        launch_pack_rows(dA, M, K, dAp, mt, c->stream);
+        launch_gemm(dWt, dAp, dC, mt, N, K, p, c->stream);
+    }
     HIPCHK(c, hipGetLastError());
     HIPCHK(c, hipStreamSynchronize(c->stream));
     std::vector<float> tmp(c_elems);
@@ -979,7 +1034,17 @@ extern "C" int bb_set_kv(bb_ctx* c, int id, int branch, int layer, const float* 
 }
 
 extern "C" int bb_debug_gemm(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
-    BB_GUARD(c, bb_debug_gemm_impl(c, A, W, C, M, N, K, split_k));
+    BB_GUARD(c, bb_debug_gemm_impl(c, A, W, C, M, N, K, split_k, 0));
+}
+
+extern "C" int bb_debug_gemm_wide(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k) {
+    BB_GUARD(c, bb_debug_gemm_impl(c, A, W, C, M, N, K, split_k, 1));
+}
+
+extern "C" int bb_debug_wide_format(bb_ctx* c, int on) {
+    if (!c) return BB_EINVAL;
+    c->wide_off = !on;
+    return BB_OK;
 }
 
 extern "C" int bb_kv_diagnostics(bb_ctx* c, int id, void* scratch, size_t scratch_bytes, double* E, double* Dpair, double* Davg) {

@@ -81,6 +81,29 @@ static inline __host__ __device__ size_t tileW_u4(int n, int k8, int ksteps) {
     return ((size_t)nt * ksteps + kstep) * 64 + lane;
 }
 
+// ---- wide format: fp16 + fp8 operands for the GEMMs of passes with many rows ----------------------------------
+// Passes over hundreds of rows are not bound by the weight stream but by what the L2 delivers to a CU and by the
+// matrix pipes, and there the second bf16 term costs a whole second pass.  Instead: activation x = hi + lo with
+// hi = fp16(x) (11 bits) and the remainder (|lo| <= 2^-12 |x|) as e5m2(lo * 2^BB_LO_SHIFT), 3 bytes per element
+// instead of 4; weights as fp16(w * 2^S) (exact: a bf16 value has 8 significant bits; S is chosen per weight row so
+// that the row's largest value lands in [2^14, 2^15)), and for the lo term the same registers converted in the
+// kernel to e4m3(w * 2^(S - BB_LO_SHIFT)), whose error (2^-4 relative) then counts 2^-16.  Per 64 k one tile costs
+// four 32x32x16 fp16 MFMAs and one 32x32x64 fp8 MFMA (twice the rate): three quarters of the two-pass matrix work.
+// The accumulator holds C * 2^S; the epilogue multiplies by 2^-S per weight row.
+// Weights: the tiled layout of the bf16 copy (tileW_u4) with fp16 values.  Activation panel:
+// [chunk = k / 64][m_tile][fragment 0..5][lane][16 bytes]:
+//   fragments 0..3: fp16, k-step ks = (k % 64) / 16, lane = row % 32 + 32 ((k / 8) % 2), element k % 8;
+//   fragments 4..5: e5m2, same lane, fragment 4 + ks / 2, byte 8 (ks % 2) + k % 8: a lane's 32 bytes are the
+//   remainders of exactly the 32 k whose fp16 weights it holds, in the order the kernel converts those.
+#define BB_WFRAGS 6
+#define BB_LO_SHIFT 8
+static inline __host__ __device__ size_t wideA_hi_u4(int m, int k8, int mt_total) {
+    return ((((size_t)(k8 >> 3) * mt_total + (m >> 5)) * BB_WFRAGS + ((k8 & 7) >> 1)) * 64) + (m & 31) + ((k8 & 1) << 5);
+}
+static inline __host__ __device__ size_t wideA_lo_byte(int m, int k8, int mt_total) {      // byte offset of 8 fp8 values
+    return (((((size_t)(k8 >> 3) * mt_total + (m >> 5)) * BB_WFRAGS + 4 + ((k8 & 7) >> 2)) * 64) + (m & 31) + ((k8 & 1) << 5)) * 16 + (((k8 >> 1) & 1) << 3);
+}
+
 // ---- KV cache layout ------------------------------------------------------------------------------
 // One block = (layer, physical row, page, kv head): the page's 64 tokens stored as the MFMA A-fragments
 // (32 rows x 16 k, 64 lanes x 8 fp16 = 1 KiB each) that attention consumes, so that a wave fetches a
@@ -114,6 +137,64 @@ static inline __host__ __device__ float bf16_to_f32(uint16_t b) {
     union { float f; uint32_t u; } v; v.u = ((uint32_t)b) << 16; return v.f;
 }
 
+// ---- fp8 encodings (round to nearest even, finite inputs) ---------------------------------------------------
+// e5m2 is the upper byte of an fp16 value; values beyond its largest finite one (57344) saturate.
+static inline __device__ uint8_t f32_to_e5m2(float x) {
+    const half_t h = (half_t)x;
+    const uint16_t b = *reinterpret_cast<const uint16_t*>(&h);
+    uint16_t r = (uint16_t)((b & 0x7FFFu) + 0x7Fu + ((b >> 8) & 1u)) >> 8;
+    if (r > 0x7Bu) r = 0x7Bu;
+    return (uint8_t)(r | ((b >> 8) & 0x80u));
+}
+// e4m3 (bias 7, no infinities, largest finite value 448, subnormals are multiples of 2^-9); saturates.
+static inline __host__ __device__ uint8_t f32_to_e4m3(float x) {
+    union { float f; uint32_t u; } v; v.f = x;
+    const uint8_t sign = (uint8_t)((v.u >> 24) & 0x80u);
+    v.u &= 0x7FFFFFFFu;
+    if (!(v.f < 448.0f)) return sign | 0x7E;
+    if (v.f < 0.015625f) return sign | (uint8_t)(int)rintf(v.f * 512.0f);       // 0..8: the subnormals, 8 = 2^-6 itself
+    const uint32_t u = v.u + 0x7FFFFu + ((v.u >> 20) & 1u);                     // round the mantissa to 3 bits
+    const uint32_t code = (((u >> 23) - 120u) << 3) | ((u >> 20) & 7u);         // exponent rebased from 127 to 7
+    return sign | (uint8_t)(code > 0x7Eu ? 0x7Eu : code);
+}
+
+#ifdef __HIPCC__
+// Eight consecutive k of one activation row into a packed panel: two bf16 terms, or (wide) fp16 + e5m2.
+static __device__ __forceinline__ void store_panel8(u32x4* Apk, int m, int k8, int mt_total, const float (&y)[8], int wide) {
+    if (!wide) {
+        uint16_t hi[8], lo[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            hi[j] = f32_to_bf16_rne(y[j]);
+            lo[j] = f32_to_bf16_rne(y[j] - bf16_to_f32(hi[j]));
+        }
+        Apk[packA_u4(m, k8, mt_total, 0)] = *reinterpret_cast<u32x4*>(hi);
+        Apk[packA_u4(m, k8, mt_total, 1)] = *reinterpret_cast<u32x4*>(lo);
+    } else {
+        typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+        f16x8_t hi;
+        uint32_t lo0 = 0u, lo1 = 0u;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float x = fminf(fmaxf(y[j], -65504.0f), 65504.0f);
+            hi[j] = (half_t)x;
+            const uint32_t b = f32_to_e5m2((x - (float)hi[j]) * (float)(1 << BB_LO_SHIFT));
+            if (j < 4) lo0 |= b << (8 * j); else lo1 |= b << (8 * (j - 4));
+        }
+        Apk[wideA_hi_u4(m, k8, mt_total)] = __builtin_bit_cast(u32x4, hi);
+        *reinterpret_cast<uint2*>(reinterpret_cast<char*>(Apk) + wideA_lo_byte(m, k8, mt_total)) = make_uint2(lo0, lo1);
+    }
+}
+static __device__ __forceinline__ void zero_panel8(u32x4* Apk, int m, int k8, int mt_total, int wide) {
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    if (!wide) { Apk[packA_u4(m, k8, mt_total, 0)] = z; Apk[packA_u4(m, k8, mt_total, 1)] = z; }
+    else {
+        Apk[wideA_hi_u4(m, k8, mt_total)] = z;
+        *reinterpret_cast<uint2*>(reinterpret_cast<char*>(Apk) + wideA_lo_byte(m, k8, mt_total)) = make_uint2(0u, 0u);
+    }
+}
+#endif
+
 // ---- running (max, rescaled sum of exponentials, argmax) of a row of logits ------------------------------
 // c = max_v softmax(l)_v = 1 / sum_v exp(l_v - max) needs only these three; ties go to the lowest token id.
 struct MSI { float m, s; int i; };
@@ -138,19 +219,27 @@ void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int 
                  GemmEpilogue epi = GemmEpilogue());
 void launch_tile_weights(const uint16_t* src, int rows, int K, u32x4* dst, int dst_row0, int interleave, hipStream_t s);
 void launch_pack_rows(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);
+// The same contraction with both operands in the wide format (fp16 + fp8 terms, see above); wscale[n] = 2^-S of weight
+// row n.  plan.nt is capped at 2; swiglu_out as in GemmEpilogue (a wide-format panel).
+void launch_gemm_wide(const u32x4* Wt, const float* wscale, const u32x4* Apk, float* P, int mt_total, int N, int K,
+                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out = nullptr);
+void launch_tile_weights_wide(const uint16_t* src, int rows, int K, u32x4* dst, float* scale_out, int dst_row0, int interleave,
+                              hipStream_t s);
+void launch_pack_rows_wide(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);
 
 void launch_embed(const Dev& D, const uint16_t* emb, float* h, int rows_cap, hipStream_t s);
+// Panels a kernel writes are two bf16 terms, or the wide format when its `wide` argument is set.
 // h += sum of split-K partials; out = packed rmsnorm(h) * gain.  gather != 0: rows are the masked (LM-head) rows.
 void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
-                         const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, hipStream_t s);
+                         const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, int wide, hipStream_t s);
 // q,k,v = sum of partials + bias; RoPE; q -> Q, k,v -> cache rows (two fp16 terms each)
 void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t partial_stride, const float* bias,
                          half_t* Q, int layer, int rows_cap, hipStream_t s);
 // act = SiLU(gate) * up from the fused (32-row interleaved) gate/up projection -> packed panel with K = f
 void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
-                            int rows_cap, int mt_total, hipStream_t s);
+                            int rows_cap, int mt_total, int wide, hipStream_t s);
 void launch_attention(const Dev& D, const half_t* Q, u32x4* Apk, int layer, int mt_total, int max_seg_rows,
-                      int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, hipStream_t s);
+                      int seg_base, int n_segs, int max_pages, float* part, size_t part_elems, int wide, hipStream_t s);
 void launch_vocab_finish(const Dev& D, int lm_cap, int bcast, hipStream_t s);
 
 void launch_pack_step(const Dev& D, int n_req, hipStream_t s);

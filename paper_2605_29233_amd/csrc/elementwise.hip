@@ -13,23 +13,8 @@ static __device__ __forceinline__ float wg_sum(float v, float* sh) {
     return t;
 }
 
-static __device__ __forceinline__ void store_split(u32x4* Apk, int m, int k8, int mt_total, const float (&y)[8]) {
-    uint16_t hi[8], lo[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        hi[j] = f32_to_bf16_rne(y[j]);
-        lo[j] = f32_to_bf16_rne(y[j] - bf16_to_f32(hi[j]));
-    }
-    Apk[packA_u4(m, k8, mt_total, 0)] = *reinterpret_cast<u32x4*>(hi);
-    Apk[packA_u4(m, k8, mt_total, 1)] = *reinterpret_cast<u32x4*>(lo);
-}
-
-static __device__ __forceinline__ void zero_packed_row(u32x4* Apk, int m, int k8s, int mt_total) {
-    u32x4 z = {0u, 0u, 0u, 0u};
-    for (int k8 = threadIdx.x; k8 < k8s; k8 += blockDim.x) {
-        Apk[packA_u4(m, k8, mt_total, 0)] = z;
-        Apk[packA_u4(m, k8, mt_total, 1)] = z;
-    }
+static __device__ __forceinline__ void zero_packed_row(u32x4* Apk, int m, int k8s, int mt_total, int wide) {
+    for (int k8 = threadIdx.x; k8 < k8s; k8 += blockDim.x) zero_panel8(Apk, m, k8, mt_total, wide);
 }
 
 // h0 = E[x]: one workgroup per packed row.
@@ -79,11 +64,11 @@ static __device__ __forceinline__ void part_sum4n(const float* __restrict__ P, i
 __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restrict__ h, const float* __restrict__ partial,
                                                            int n_partial, size_t partial_stride,
                                                            const float* __restrict__ gain, u32x4* __restrict__ Apk,
-                                                           int mt_total, int gather, int bcast) {
+                                                           int mt_total, int gather, int bcast, int wide) {
     __shared__ float sh[4];
     const int j = blockIdx.x, d = D.d, k8s = d >> 3;
     const int count = gather ? D.counts[1] : D.counts[0];
-    if (j >= count) { zero_packed_row(Apk, j, k8s, mt_total); return; }
+    if (j >= count) { zero_packed_row(Apk, j, k8s, mt_total, wide); return; }
     const int r = gather ? D.lm_row[j] : j;
     float* hr = h + (size_t)r * d;
     // the row stays in registers between the two passes: thread t owns the 8-column groups t, t + 256, ...
@@ -129,7 +114,7 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restr
         float y[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) y[q] = v[i][q] * inv * gg[q];
-        store_split(Apk, j, k8, mt_total, y);
+        store_panel8(Apk, j, k8, mt_total, y, wide);
         if (gather)
             for (int b = 0; b < nb; ++b) {
                 float* dst = D.map_hf + (mrow + (size_t)b * D.gmax) * d + k8 * 8;
@@ -144,7 +129,8 @@ __global__ __launch_bounds__(256) void rmsnorm_pack_kernel(Dev D, float* __restr
 // instead of eight workgroups storing 16 bytes each.  d <= 4096 (two column groups per thread).
 __global__ __launch_bounds__(256) void rmsnorm_pack8_kernel(Dev D, float* __restrict__ h, const float* __restrict__ partial,
                                                             int n_partial, size_t partial_stride,
-                                                            const float* __restrict__ gain, u32x4* __restrict__ Apk, int mt_total) {
+                                                            const float* __restrict__ gain, u32x4* __restrict__ Apk, int mt_total,
+                                                            int wide) {
     constexpr int R = 8, G = 2;
     __shared__ float sh[4][R];
     const int j0 = blockIdx.x * R, d = D.d, k8s = d >> 3, count = D.counts[0], t = threadIdx.x;
@@ -192,6 +178,16 @@ __global__ __launch_bounds__(256) void rmsnorm_pack8_kernel(Dev D, float* __rest
         if (k8 >= k8s) break;
         const float4 g0 = reinterpret_cast<const float4*>(gain)[2 * k8], g1 = reinterpret_cast<const float4*>(gain)[2 * k8 + 1];
         const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        if (wide) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {           // rows past the count hold zeros
+                float y[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) y[q] = v[r][i][q] * inv[r] * gg[q];
+                store_panel8(Apk, j0 + r, k8, mt_total, y, 1);
+            }
+            continue;
+        }
 #pragma unroll
         for (int term = 0; term < 2; ++term)
 #pragma unroll
@@ -209,13 +205,13 @@ __global__ __launch_bounds__(256) void rmsnorm_pack8_kernel(Dev D, float* __rest
 }
 
 void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
-                         const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, hipStream_t s) {
+                         const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, int wide, hipStream_t s) {
     // eight rows per workgroup once that still gives every CU a workgroup, or when a row is too short to occupy
     // one (d <= 512: at most 64 of the 256 threads have a column group)
     if (!gather && D.d <= 4096 && mt_total * 32 > 256 && (mt_total * 4 >= 256 || D.d <= 512))
-        rmsnorm_pack8_kernel<<<mt_total * 4, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total);
+        rmsnorm_pack8_kernel<<<mt_total * 4, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, wide);
     else
-        rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, gather, bcast);
+        rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, gather, bcast, wide);
 }
 
 static __device__ __forceinline__ void put2(half_t* hi_p, half_t* lo_p, float y) {
@@ -355,14 +351,13 @@ void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t p
 // same features, so feature f has its gate in column (f / 32) * 64 + f % 32 and its up 32 further.
 __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float* __restrict__ gu, int n_partial,
                                                               size_t partial_stride, int ldp, u32x4* __restrict__ Apk,
-                                                              int mt_total) {
+                                                              int mt_total, int wide) {
     const int f8s = (D.f + 63) / 64 * 8;                   // the panel's K is padded to whole chunks of 64 with zeros
     const size_t it = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int m = (int)(it / f8s), f = (int)(it % f8s) * 8;
     if (m >= mt_total * 32) return;
     if (m >= D.counts[0] || f >= D.f) {
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        Apk[packA_u4(m, f >> 3, mt_total, 0)] = z; Apk[packA_u4(m, f >> 3, mt_total, 1)] = z;
+        zero_panel8(Apk, m, f >> 3, mt_total, wide);
         return;
     }
     const size_t off = (size_t)m * ldp + (f >> 5) * 64 + (f & 31);
@@ -375,14 +370,14 @@ __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float
     float y[8];
 #pragma unroll
     for (int q = 0; q < 8; ++q) y[q] = g[q] / (1.0f + expf(-g[q])) * u[q];
-    store_split(Apk, m, f >> 3, mt_total, y);
+    store_panel8(Apk, m, f >> 3, mt_total, y, wide);
 }
 
 void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
-                            int rows_cap, int mt_total, hipStream_t s) {
+                            int rows_cap, int mt_total, int wide, hipStream_t s) {
     (void)rows_cap;
     const size_t items = (size_t)mt_total * 32 * ((D.f + 63) / 64 * 8);
-    swiglu_epilogue_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(D, gu, n_partial, partial_stride, ldp, Apk, mt_total);
+    swiglu_epilogue_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(D, gu, n_partial, partial_stride, ldp, Apk, mt_total, wide);
 }
 
 // Second half of the vocabulary reduction.  The LM-head GEMM leaves one (max, rescaled sum of exponentials,

@@ -143,13 +143,16 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     };
 
     u32x4 w[DW][KC][NT], a[A_PER_THREAD], b[2][MT][BB_SPLIT];
-    // prologue: chunk c0 staged, chunk c0+1 in registers, weights of c0 and c0+1 in flight
+    // prologue: chunk c0 staged, chunk c0+1 in registers, weights of c0 and c0+1 in flight.  The loads are issued in
+    // the order the loop issues them (activations of a chunk, then the weights of the same chunk): the wait counts at
+    // the loop head are the more cautious of the two ways in, and with any other order the first chunk of every
+    // round would wait for every load in flight.
     load_a(a, c0);
     load_w(w[0], c0, 0, KC);
-    load_w(w[1], c0 + 1, 0, KC);
 #pragma unroll
     for (int i = 0; i < A_PER_THREAD; ++i) lds[0][i * 256 + threadIdx.x] = a[i];
     load_a(a, c0 + 1);
+    load_w(w[1], c0 + 1, 0, KC);
     __syncthreads();
     read_b(b[0], 0, 0);
 

@@ -47,6 +47,28 @@ def test_mfma_gemm_matches_fp64(bb, M, N, K, split):
     assert err <= 2e-5 * scale * max(1.0, (K / 256) ** 0.5), (err, scale)
 
 
+@pytest.mark.parametrize("M,N,K,split", [
+    (32, 32, 16, 1), (1, 64, 32, 1), (56, 768, 256, 0), (37, 256, 688, 0), (130, 1024, 256, 0),
+    (300, 96, 4096, 7), (384, 1376, 256, 0), (700, 4608, 512, 0), (1536, 5632, 128, 0), (3000, 512, 2752, 2),
+])
+def test_wide_format_gemm_matches_fp64(bb, M, N, K, split):
+    """The fp16 + fp8 operand kernel of the passes with many rows: activation = fp16 term + e5m2 remainder,
+    weight = row-scaled fp16 (exact) and e4m3.  Per product the error is about 2^-16 relative (e4m3 rounding of
+    the weight times the 2^-12 remainder, e5m2 rounding of the remainder), random in sign."""
+    rng = np.random.default_rng(M * 11 + N)
+    A = (rng.standard_normal((M, K)) * np.exp(rng.uniform(-3, 3, (M, 1)))).astype(np.float32)     # rows of very different size
+    Wb = gen_normal_bf16(1, f"w{N}x{K}", N * K, 0.05).view(torch.int16).numpy().view(np.uint16).reshape(N, K).copy()
+    Wb[0::7] = ((Wb[0::7].astype(np.uint32) << 16).view(np.float32) * 2.0 ** -12).view(np.uint32) >> 16   # some tiny rows
+    W = (Wb.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    print(f"wide gemm case M={M} N={N} K={K} split={split}", flush=True)
+    C = bb.debug_gemm(A, Wb, split, wide=True)
+    ref = A.astype(np.float64) @ W.T
+    # error scale of one output: |a| . |w| (sum of magnitudes), of which a random 2^-15 per term survives
+    mag = np.abs(A).astype(np.float64) @ np.abs(W).T
+    err = np.abs(C - ref)
+    assert (err <= 2.0 ** -13 * mag / np.sqrt(K) * 4 + 1e-30).all(), float((err / (mag + 1e-300)).max())
+
+
 @pytest.mark.parametrize("hq,hkv,hd,bias", [(4, 2, 64, True), (2, 1, 128, False), (6, 2, 64, True)])
 def test_qkv_projection_gives_the_same_cache_and_logits_under_every_plan(hq, hkv, hd, bias):
     """The q|k|v projection of the block forward with tiles of 128, 256 or 384 columns and with k whole or split in
