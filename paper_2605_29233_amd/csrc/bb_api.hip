@@ -90,8 +90,12 @@ struct Bump {
     }
 };
 
-// Passes over more rows than this are bound by the matrix pipes: their layer GEMMs take the wide format.
+// Passes over more rows than BB_SKINNY_ROWS count as bound by the matrix pipes in the profile classes.  The layer
+// GEMMs take the wide format as soon as there is more than one group of 128 rows: from then on every weight panel is
+// multiplied with two activation panels and the matrix work, not the weight stream, sets the time (measured: 9 %
+// faster at 240 rows, 5-10 % slower at 120 rows, where the two-term kernel's streaming loads win).
 #define BB_SKINNY_ROWS 256
+#define BB_WIDE_FORMAT_ROWS 128
 
 // Largest split-K output over every row count the forward may be called with.
 static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
@@ -100,7 +104,7 @@ static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
         GemmPlan p = gemm_plan(rows, N, K, 0, rows > 128 ? forced_nt_wide : 0);
         size_t e = (size_t)p.split_k * rows * N;
         if (e > best) best = e;
-        if (rows > BB_SKINNY_ROWS) {        // wide-format kernel: the plan's own tile width, or two tiles for gate/up
+        if (rows > BB_WIDE_FORMAT_ROWS) {   // wide-format kernel: the plan's own tile width, or two tiles for gate/up
             p = gemm_plan(rows, N, K, 0, forced_nt_wide);
             e = (size_t)p.split_k * rows * N;
             if (e > best) best = e;
@@ -454,7 +458,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const int gk = rows_cap <= BB_SKINNY_ROWS ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
     // many rows: the layer GEMMs are bound by the matrix pipes and run in the wide format (every kernel that writes
     // a panel for them is told so); the LM head keeps two bf16 terms (its rows are the masked ones only)
-    const int wide = rows_cap > BB_SKINNY_ROWS && !c->wide_off;
+    const int wide = rows_cap > BB_WIDE_FORMAT_ROWS && !c->wide_off;
     // kind: 0 LM head, 1 O/down, 2 gate/up, 3 QKV (index of the tuning overrides)
     // swiglu_out: where the gate/up projection may put SiLU(gate) * up itself; it does when its k range
     // is not split (then 0 is returned and no partial sums exist)
