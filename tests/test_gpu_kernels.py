@@ -110,3 +110,46 @@ def test_qkv_projection_gives_the_same_cache_and_logits_under_every_plan(hq, hkv
         for (K, V), (Kr, Vr) in zip(kv, ref_kv):
             assert np.abs(K - Kr).max() <= 1e-5 * max(1.0, np.abs(Kr).max()), key
             assert np.abs(V - Vr).max() <= 1e-5 * max(1.0, np.abs(Vr).max()), key
+
+
+def test_wide_format_forward_agrees_with_two_bf16_terms():
+    """A periodic refresh (3 x 150 rows: wide format) followed by block steps of 240 rows (wide format as well) against
+    the same calls with the wide format switched off (two bf16 terms everywhere): caches agree to a few 1e-4 of their
+    scale (the fp16 + fp8 products are good to about 2^-16 each), logits to well inside the parity tolerance."""
+    from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT, BB_PERIODIC
+    from workload.gen import gen_weights, gen_prompt
+    shape = ModelShape("widetest", 3, 512, 8, 2, 64, 1376 + 16, 2048, qkv_bias=True)      # d_ffn % 64 != 0: padded panels
+    decode = DecodeParams(0.9, 0.5, 4, 2)
+    weights = dict(gen_weights(shape, 5))
+    prompt = gen_prompt(shape, 5, 0, 22)
+    G, blocks = 128, (16, 96, 128)
+    res = {}
+    for wide in (True, False):
+        b = BlockBatch(shape, decode, Limits(1, 3, 22 + G, G, 240), poison_workspace=True)
+        try:
+            b.load_weights(weights.items())
+            b.keep_logits(True)
+            b.wide_format(wide)
+            rid = b.request_open(prompt, G, blocks)
+            b.refresh([rid], BB_INIT)
+            b.merge_commit([rid])
+            outs = []
+            for step in range(3):
+                v = b.denoise_step([rid])
+                assert v.m_q == 240
+                outs.append((v.logits().copy(), v.argmax().copy()))
+                st = b.merge_commit([rid])[0]
+                if st.refresh_due:
+                    b.refresh([rid], BB_PERIODIC)
+            res[wide] = (outs, [b.get_kv(rid, k, l) for k in range(3) for l in range(3)], b.get_tokens(rid))
+        finally:
+            b.close()
+    (ow, kvw, Xw), (ob, kvb, Xb) = res[True], res[False]
+    worst = 0.0
+    for (lw, aw), (lb, ab) in zip(ow, ob):
+        assert lw.shape == lb.shape
+        worst = max(worst, float(np.abs(lw[:, :-1] - lb[:, :-1]).max()))
+    print("wide vs two-term: max logit difference", worst, flush=True)
+    assert worst <= 5e-3
+    for (Kw, Vw), (Kb, Vb) in zip(kvw, kvb):
+        assert np.abs(Kw - Kb).max() <= 5e-4 * np.abs(Kb).max() and np.abs(Vw - Vb).max() <= 5e-4 * np.abs(Vb).max()
