@@ -30,7 +30,7 @@ struct bb_ctx {
     std::vector<char> loaded;           // per tensor slot
     int n_expected;
     // activations
-    float *h, *qkv, *part, *gu, *logits, *dbg, *attn_part, *wscales;
+    float *h, *qkv, *part, *gu, *logits, *dbg, *attn_part, *wscales, *ssq;
     size_t attn_part_elems;
     u32x4 *Apk, *Apk2; half_t* Q; char* stage;     // Apk2: SwiGLU output panel (written while Apk is still being read)
     size_t qkv_elems, part_elems, gu_elems, stage_bytes, dbg_bytes;
@@ -196,6 +196,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     // split-KV partial results of block-step attention: up to 8 splits of every 32-row tile
     c->attn_part_elems = ((size_t)l.max_step_rows * (m.n_q_heads / m.n_kv_heads) / 32 + nbr) * m.n_kv_heads * 8 * (64 + 32 * m.head_dim);
     c->attn_part = b.take<float>(c->attn_part_elems);
+    c->ssq = b.take<float>((size_t)(BB_WIDE_FORMAT_ROWS + 31) / 32 * 32 * ((m.d_model + 2047) / 2048));     // block sums of squares of the rows of a block step
     c->dbg_bytes = 2 * (size_t)lpad * m.n_kv_heads * m.head_dim * sizeof(float);
     c->dbg = b.take<float>(c->dbg_bytes / sizeof(float));
     size_t biggest = (size_t)m.vocab * m.d_model;
@@ -459,6 +460,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     // many rows: the layer GEMMs are bound by the matrix pipes and run in the wide format (every kernel that writes
     // a panel for them is told so); the LM head keeps two bf16 terms (its rows are the masked ones only)
     const int wide = rows_cap > BB_WIDE_FORMAT_ROWS && !c->wide_off;
+    const bool defer = rows_cap <= BB_WIDE_FORMAT_ROWS;     // block steps of at most 128 rows: every gate/up GEMM has a k split, its consumer is the SwiGLU kernel
     // kind: 0 LM head, 1 O/down, 2 gate/up, 3 QKV (index of the tuning overrides)
     // swiglu_out: where the gate/up projection may put SiLU(gate) * up itself; it does when its k range
     // is not split (then 0 is returned and no partial sums exist)
@@ -476,7 +478,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         const int nt = c->force_nt[kind] > 0 ? c->force_nt[kind] : (swiglu_out && rows > 128 ? 2 : 0);
         GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, nt);
         if (c->force_split[kind] > 0 && kind != 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
-        const bool fused = swiglu_out && p.split_k == 1 && p.nt == 2;
+        const bool fused = swiglu_out && !defer && p.split_k == 1 && p.nt == 2;     // (with a deferred norm scale SwiGLU needs the separate kernel)
         PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
         GemmEpilogue epi; epi.swiglu_out = fused ? swiglu_out : nullptr;
         launch_gemm(W, A, P, mtt, N, K, p, s, epi);
@@ -489,17 +491,24 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const size_t pstride = (size_t)rows_pad * d;
     for (int li = 0; li < m.n_layers; ++li) {
         const LayerW& W = c->layers[li];
-        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, 0, 0, wide, s); }
+        // few rows: the norm's scale is applied after the projection (see residual_pack_kernel)
+        const float* ssq = defer ? c->ssq : nullptr;
+        int nblk = 0;
+        { PROF(BB_K_GLUE, 0, 0);
+          if (defer) nblk = launch_residual_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, c->ssq, s);
+          else launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, 0, 0, wide, s); }
         const int s_qkv = gemm(3, W.wqkv, W.wqkv_w, W.s_qkv, c->Apk, c->qkv, nqkv, d, rows_cap, mt, gk);
         { PROF(BB_K_GLUE, 0, 0);
-          launch_qkv_epilogue(D, c->qkv, s_qkv, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, s); }
+          launch_qkv_epilogue(D, c->qkv, s_qkv, (size_t)rows_pad * nqkv, m.qkv_bias ? W.bqkv : nullptr, c->Q, li, rows_cap, ssq, nblk, s); }
         if (mode == 2 && li == m.n_layers - 1) break;
         { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, max_pages, c->attn_part, c->attn_part_elems, wide, s); }
         const int s_o = gemm(1, W.wo, W.wo_w, W.s_o, c->Apk, c->part, d, nq, rows_cap, mt, gk);
-        { PROF(BB_K_GLUE, 0, 0); launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, wide, s); }
+        { PROF(BB_K_GLUE, 0, 0);
+          if (defer) nblk = launch_residual_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, c->ssq, s);
+          else launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, wide, s); }
         const int s_gu = gemm(2, W.wgu, W.wgu_w, W.s_gu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, c->Apk2);
         if (s_gu > 0) { PROF(BB_K_GLUE, 0, 0);
-          launch_swiglu_epilogue(D, c->gu, s_gu, (size_t)rows_pad * ngu, ngu, c->Apk2, rows_cap, mt, wide, s); }
+          launch_swiglu_epilogue(D, c->gu, s_gu, (size_t)rows_pad * ngu, ngu, c->Apk2, rows_cap, mt, wide, ssq, nblk, s); }
         s_down = gemm(1, W.wdown, W.wdown_w, W.s_down, c->Apk2, c->part, d, f, rows_cap, mt, gk);
     }
     if (mode != 2) {

@@ -214,6 +214,64 @@ void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_par
         rmsnorm_pack_kernel<<<mt_total * 32, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, gather, bcast, wide);
 }
 
+// Few rows (block steps): the norm's row-wide sum would leave one workgroup per row with the whole row's partial tiles
+// to read, and half the CUs idle.  RMSNorm's scale is one number per row and commutes with the projection that follows:
+// (x / rms(x) * gain) W^T = (x * gain) W^T / rms(x).  So this kernel only adds the split-K partials to the residual,
+// packs x * gain (two bf16 terms) and leaves the sum of squares of each 2048-column block in ssq[row][block]; the kernels
+// that consume the projection (bias + RoPE + cache write, SwiGLU) multiply by 1 / sqrt(sum / d + eps).  One workgroup
+// per (row, block of 2048 columns), one 8-column group per thread.
+#define BB_SSQ_BLOCK 2048
+__global__ __launch_bounds__(256) void residual_pack_kernel(Dev D, float* __restrict__ h, const float* __restrict__ partial,
+                                                            int n_partial, size_t partial_stride,
+                                                            const float* __restrict__ gain, u32x4* __restrict__ Apk,
+                                                            int mt_total, float* __restrict__ ssq, int nblk) {
+    __shared__ float sh[4];
+    const int j = blockIdx.x / nblk, b = blockIdx.x % nblk, d = D.d, k8 = b * (BB_SSQ_BLOCK / 8) + threadIdx.x;
+    const bool live = k8 < (d >> 3);
+    if (j >= D.counts[0]) {
+        if (live) zero_panel8(Apk, j, k8, mt_total, 0);
+        if (threadIdx.x == 0) ssq[j * nblk + b] = 0.f;
+        return;
+    }
+    float ss = 0.f;
+    if (live) {
+        float* hr = h + (size_t)j * d;
+        const float4 a = reinterpret_cast<const float4*>(hr)[2 * k8], c = reinterpret_cast<const float4*>(hr)[2 * k8 + 1];
+        float4 p[2] = {make_float4(0.f, 0.f, 0.f, 0.f), make_float4(0.f, 0.f, 0.f, 0.f)};
+        if (n_partial) {
+            const size_t off[2] = {(size_t)j * d + k8 * 8, (size_t)j * d + k8 * 8 + 4};
+            part_sum4n<2>(partial, n_partial, partial_stride, off, p);
+        }
+        const float v[8] = {a.x + p[0].x, a.y + p[0].y, a.z + p[0].z, a.w + p[0].w, c.x + p[1].x, c.y + p[1].y, c.z + p[1].z, c.w + p[1].w};
+        if (n_partial) {
+            reinterpret_cast<float4*>(hr)[2 * k8] = make_float4(v[0], v[1], v[2], v[3]);
+            reinterpret_cast<float4*>(hr)[2 * k8 + 1] = make_float4(v[4], v[5], v[6], v[7]);
+        }
+        const float4 g0 = reinterpret_cast<const float4*>(gain)[2 * k8], g1 = reinterpret_cast<const float4*>(gain)[2 * k8 + 1];
+        const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+        float y[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) { ss += v[q] * v[q]; y[q] = v[q] * gg[q]; }
+        store_panel8(Apk, j, k8, mt_total, y, 0);
+    }
+    ss = wg_sum(ss, sh);
+    if (threadIdx.x == 0) ssq[j * nblk + b] = ss;
+}
+
+int launch_residual_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
+                         const float* gain, u32x4* Apk, int mt_total, float* ssq, hipStream_t s) {
+    const int nblk = (D.d + BB_SSQ_BLOCK - 1) / BB_SSQ_BLOCK;
+    residual_pack_kernel<<<mt_total * 32 * nblk, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, ssq, nblk);
+    return nblk;
+}
+
+// 1 / rms of a row from the block sums residual_pack_kernel left (fixed order, the same in every consumer)
+static __device__ __forceinline__ float row_inv_rms(const Dev& D, const float* __restrict__ ssq, int nblk, int m) {
+    float t = 0.f;
+    for (int b = 0; b < nblk; ++b) t += ssq[m * nblk + b];
+    return 1.0f / sqrtf(t / (float)D.d + D.rms_eps);
+}
+
 static __device__ __forceinline__ void put2(half_t* hi_p, half_t* lo_p, float y) {
     const half_t hi = (half_t)y;
     *hi_p = hi;
@@ -238,7 +296,8 @@ static __device__ __forceinline__ void put2x4(half_t* hi_p, half_t* lo_p, const 
 // in the V fragments.
 __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* __restrict__ qkv, int n_partial,
                                                            size_t partial_stride, const float* __restrict__ bias,
-                                                           half_t* __restrict__ Q, int layer) {
+                                                           half_t* __restrict__ Q, int layer,
+                                                           const float* __restrict__ ssq, int nblk) {
     __shared__ float tile[128][17];
     const int m0 = blockIdx.x * 16, c0 = blockIdx.y * 128, t = threadIdx.x;
     const int count = D.counts[0];
@@ -258,6 +317,10 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
         float4 xs[2];
         part_sum4n<2>(qkv, n_partial, partial_stride, offs, xs);
         float4 x1 = xs[0], x2 = xs[1];
+        if (ssq) {          // the projection's input was packed without its RMSNorm scale
+            const float inv = row_inv_rms(D, ssq, nblk, m);
+            x1.x *= inv; x1.y *= inv; x1.z *= inv; x1.w *= inv; x2.x *= inv; x2.y *= inv; x2.z *= inv; x2.w *= inv;
+        }
         if (bias) {
             const float4 b1 = *reinterpret_cast<const float4*>(&bias[ch + j]);
             const float4 b2 = *reinterpret_cast<const float4*>(&bias[ch + j + half]);
@@ -294,6 +357,10 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
             float4 vs[2];
             part_sum4n<2>(qkv, n_partial, partial_stride, offs, vs);
             float4 v0 = vs[0], v1 = vs[1];
+            if (ssq) {
+                const float inv = row_inv_rms(D, ssq, nblk, m);
+                v0.x *= inv; v0.y *= inv; v0.z *= inv; v0.w *= inv; v1.x *= inv; v1.y *= inv; v1.z *= inv; v1.w *= inv;
+            }
             if (bias) {
                 const float4 b0 = *reinterpret_cast<const float4*>(&bias[c0 + cg]);
                 const float4 b1 = *reinterpret_cast<const float4*>(&bias[c0 + cg + 4]);
@@ -342,16 +409,16 @@ __global__ __launch_bounds__(256) void qkv_epilogue_kernel(Dev D, const float* _
 }
 
 void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t partial_stride, const float* bias,
-                         half_t* Q, int layer, int rows_cap, hipStream_t s) {
+                         half_t* Q, int layer, int rows_cap, const float* ssq, int nblk, hipStream_t s) {
     dim3 grid((rows_cap + 15) / 16, D.nqkv / 128);
-    qkv_epilogue_kernel<<<grid, 256, 0, s>>>(D, qkv, n_partial, partial_stride, bias, Q, layer);
+    qkv_epilogue_kernel<<<grid, 256, 0, s>>>(D, qkv, n_partial, partial_stride, bias, Q, layer, ssq, nblk);
 }
 
 // act = SiLU(gate) * up.  The fused matrix alternates 32 gate rows with the 32 up rows of the
 // same features, so feature f has its gate in column (f / 32) * 64 + f % 32 and its up 32 further.
 __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float* __restrict__ gu, int n_partial,
                                                               size_t partial_stride, int ldp, u32x4* __restrict__ Apk,
-                                                              int mt_total, int wide) {
+                                                              int mt_total, int wide, const float* __restrict__ ssq, int nblk) {
     const int f8s = (D.f + 63) / 64 * 8;                   // the panel's K is padded to whole chunks of 64 with zeros
     const size_t it = (size_t)blockIdx.x * 256 + threadIdx.x;
     const int m = (int)(it / f8s), f = (int)(it % f8s) * 8;
@@ -367,17 +434,18 @@ __global__ __launch_bounds__(256) void swiglu_epilogue_kernel(Dev D, const float
     const float4 g0 = gs[0], g1 = gs[1], u0 = gs[2], u1 = gs[3];
     const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
     const float u[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+    const float inv = ssq ? row_inv_rms(D, ssq, nblk, m) : 1.0f;      // input packed without its RMSNorm scale
     float y[8];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) y[q] = g[q] / (1.0f + expf(-g[q])) * u[q];
+    for (int q = 0; q < 8; ++q) { const float gq = g[q] * inv; y[q] = gq / (1.0f + expf(-gq)) * (u[q] * inv); }
     store_panel8(Apk, m, f >> 3, mt_total, y, wide);
 }
 
 void launch_swiglu_epilogue(const Dev& D, const float* gu, int n_partial, size_t partial_stride, int ldp, u32x4* Apk,
-                            int rows_cap, int mt_total, int wide, hipStream_t s) {
+                            int rows_cap, int mt_total, int wide, const float* ssq, int nblk, hipStream_t s) {
     (void)rows_cap;
     const size_t items = (size_t)mt_total * 32 * ((D.f + 63) / 64 * 8);
-    swiglu_epilogue_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(D, gu, n_partial, partial_stride, ldp, Apk, mt_total, wide);
+    swiglu_epilogue_kernel<<<(unsigned)((items + 255) / 256), 256, 0, s>>>(D, gu, n_partial, partial_stride, ldp, Apk, mt_total, wide, ssq, nblk);
 }
 
 // Second half of the vocabulary reduction.  The LM-head GEMM leaves one (max, rescaled sum of exponentials,
