@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256, 1) void gemm_kernel(const u32x4* __restrict__ 
     // prologue: chunk c0 staged, chunk c0+1 in registers, weights of c0 and c0+1 in flight.  The loads are issued in
     // the order the loop issues them (activations of a chunk, then the weights of the same chunk): the wait counts at
     // the loop head are the more cautious of the two ways in, and with any other order the first chunk of every
-    // round would wait for every load in flight.
+    // pass through the unrolled loop body would wait for every load in flight.
     load_a(a, c0);
     load_w(w[0], c0, 0, KC);
 #pragma unroll
