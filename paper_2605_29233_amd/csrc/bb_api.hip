@@ -55,25 +55,31 @@ struct bb_ctx {
 // Bracket one launch with events when profiling is on.  Inside a forward the launches follow each other
 // without anything in between, so the end event of one launch also serves as the start of the next:
 // one event packet per kernel boundary keeps the timeline close to the unprofiled one.
+//
+// stamped = true (the GEMM launches): the scope's two events are not recorded around the launch but handed to it and
+// receive the begin and end time stamps of its dispatch packet, i.e. the kernel's own duration as a profiler's
+// dispatch records show it, with no packet added to the stream.
 struct ProfScope {
-    bb_ctx* c; int idx;
-    ProfScope(bb_ctx* c_, int klass, double bytes, double flops) : c(c_), idx(-1) {
+    bb_ctx* c; int idx; bool stamped;
+    ProfScope(bb_ctx* c_, int klass, double bytes, double flops, bool stamped_ = false) : c(c_), idx(-1), stamped(stamped_) {
         if (!c->prof_on) return;
         auto get = [&]() { hipEvent_t e; if (c->ev_pool.empty()) { if (hipEventCreate(&e) != hipSuccess) return (hipEvent_t) nullptr; }
                            else { e = c->ev_pool.back(); c->ev_pool.pop_back(); } return e; };
-        const bool chain = c->prof_chain && c->prof_prev_end;
+        const bool chain = !stamped && c->prof_chain && c->prof_prev_end;
         bb_ctx::ProfRec r{chain ? c->prof_prev_end : get(), get(), klass, bytes, flops, !chain};
         if (!r.a || !r.b) return;
-        if (!chain) (void)hipEventRecord(r.a, c->stream);
+        if (!chain && !stamped) (void)hipEventRecord(r.a, c->stream);
         c->prof.push_back(r); idx = (int)c->prof.size() - 1;
     }
+    LaunchStamps stamps() const { LaunchStamps st; if (idx >= 0 && stamped) { st.start = c->prof[idx].a; st.stop = c->prof[idx].b; } return st; }
     ~ProfScope() {
         if (idx < 0) return;
-        (void)hipEventRecord(c->prof[idx].b, c->stream);
+        if (!stamped) (void)hipEventRecord(c->prof[idx].b, c->stream);
         c->prof_prev_end = c->prof[idx].b;
     }
 };
 #define PROF(klass, bytes, flops) ProfScope prof_scope_(c, klass, bytes, flops)
+#define PROF_STAMPED(klass, bytes, flops) ProfScope prof_scope_(c, klass, bytes, flops, true)
 
 static int fail(bb_ctx* c, int code, const std::string& msg) { if (c) c->err = msg; return code; }
 #define HIPCHK(c, expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) \
@@ -470,8 +476,8 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
             // the fused SwiGLU epilogue pairs two tiles per wave; otherwise the plan picks the tile width
             GemmPlan p = gemm_plan(rows, N, K, 0, swiglu_out ? 2 : 0);
             const bool fused = swiglu_out && p.split_k == 1 && p.nt == 2;
-            PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-            launch_gemm_wide(Ww, wscale, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr);
+            PROF_STAMPED(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
+            launch_gemm_wide(Ww, wscale, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr, prof_scope_.stamps());
             return fused ? 0 : p.split_k;
         }
         // with many rows the gate/up projection keeps 256-column tiles: its fused SwiGLU epilogue pairs two tiles per wave
@@ -479,9 +485,9 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, nt);
         if (c->force_split[kind] > 0 && kind != 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
         const bool fused = swiglu_out && !defer && p.split_k == 1 && p.nt == 2;     // (with a deferred norm scale SwiGLU needs the separate kernel)
-        PROF(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
+        PROF_STAMPED(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
         GemmEpilogue epi; epi.swiglu_out = fused ? swiglu_out : nullptr;
-        launch_gemm(W, A, P, mtt, N, K, p, s, epi);
+        launch_gemm(W, A, P, mtt, N, K, p, s, epi, prof_scope_.stamps());
         return fused ? 0 : p.split_k;
     };
     c->prof_chain = false;              // the first launch records its own start
@@ -518,8 +524,8 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         {   // LM head with the vocabulary reduction in its epilogue: no k split, 256-column tiles (128 for tiny vocabularies)
             GemmPlan p = gemm_plan(lm_cap, m.vocab, d, 1, m.vocab / 32 >= 8 ? 2 : 1);
             GemmEpilogue epi; epi.vocab_part = D.vr_part; epi.mask_id = m.mask_id; epi.keep_logits = c->keep_logits;
-            PROF(lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE, 2.0 * m.vocab * d, 2.0 * lm_cap * (double)m.vocab * d);
-            launch_gemm(c->lm, c->Apk, c->logits, mt_lm, m.vocab, d, p, s, epi);
+            PROF_STAMPED(lm_cap <= 256 ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE, 2.0 * m.vocab * d, 2.0 * lm_cap * (double)m.vocab * d);
+            launch_gemm(c->lm, c->Apk, c->logits, mt_lm, m.vocab, d, p, s, epi, prof_scope_.stamps());
         }
         { PROF(BB_K_GLUE, 0, 0); launch_vocab_finish(D, lm_cap, mode == 1, s); }
     }

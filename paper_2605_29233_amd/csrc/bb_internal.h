@@ -215,14 +215,17 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt);
 // (swiglu_out, needs nt == 2 and no k split); or the vocabulary reduction of the LM head (vocab_part: per row and
 // column tile one (max, sum, argmax); needs no k split and nt <= 2; P is then written only if keep_logits).
 struct GemmEpilogue { u32x4* swiglu_out = nullptr; float4* vocab_part = nullptr; int mask_id = -1; int keep_logits = 1; };
+// Optional events that receive the begin and end time stamps of the launch's own dispatch packet (profiling): unlike
+// events recorded around a launch they add no packets to the stream and exclude the gap before the kernel.
+struct LaunchStamps { hipEvent_t start = nullptr; hipEvent_t stop = nullptr; };
 void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s,
-                 GemmEpilogue epi = GemmEpilogue());
+                 GemmEpilogue epi = GemmEpilogue(), LaunchStamps st = LaunchStamps());
 void launch_tile_weights(const uint16_t* src, int rows, int K, u32x4* dst, int dst_row0, int interleave, hipStream_t s);
 void launch_pack_rows(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);
 // The same contraction with both operands in the wide format (fp16 + fp8 terms, see above); wscale[n] = 2^-S of weight
 // row n.  plan.nt is capped at 2; swiglu_out as in GemmEpilogue (a wide-format panel).
 void launch_gemm_wide(const u32x4* Wt, const float* wscale, const u32x4* Apk, float* P, int mt_total, int N, int K,
-                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out = nullptr);
+                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out = nullptr, LaunchStamps st = LaunchStamps());
 void launch_tile_weights_wide(const uint16_t* src, int rows, int K, u32x4* dst, float* scale_out, int dst_row0, int interleave,
                               hipStream_t s);
 void launch_pack_rows_wide(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);

@@ -10,6 +10,7 @@
 // is split over several workgroups to occupy every CU; each writes its partial tile and the
 // consumer kernel (residual + norm, SwiGLU, bias + RoPE + cache write) sums them in split order.
 #include "bb_internal.h"
+#include <hip/hip_ext.h>
 #include <type_traits>
 #include <algorithm>
 
@@ -365,24 +366,24 @@ GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt) {
 }
 
 void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int N, int K, GemmPlan plan, hipStream_t s,
-                 GemmEpilogue epi) {
+                 GemmEpilogue epi, LaunchStamps st) {
     const int n_tiles = N / 32, ksteps = (K + 63) / 64 * 4, m_groups = (mt_total + MT - 1) / MT;     // K padded to whole chunks
     const size_t split_stride = (size_t)mt_total * 32 * N;
     const int tiles_x = (n_tiles + 4 * plan.nt - 1) / (4 * plan.nt);
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
 #define GEMM_ARGS Wt, Apk, P, split_stride, N, mt_total, n_tiles, ksteps, plan.chunks_per_split, tiles_x, m_groups, epi.swiglu_out, epi.vocab_part, epi.mask_id, epi.keep_logits
     if (epi.swiglu_out)
-        gemm_kernel<2, EPI_SWIGLU><<<grid, 256, 0, s>>>(GEMM_ARGS);
+        hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_kernel<2, EPI_SWIGLU>), grid, dim3(256), 0, s, st.start, st.stop, 0, GEMM_ARGS);
     else if (epi.vocab_part && plan.nt == 2)
-        gemm_kernel<2, EPI_VOCAB><<<grid, 256, 0, s>>>(GEMM_ARGS);
+        hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_kernel<2, EPI_VOCAB>), grid, dim3(256), 0, s, st.start, st.stop, 0, GEMM_ARGS);
     else if (epi.vocab_part)
-        gemm_kernel<1, EPI_VOCAB><<<grid, 256, 0, s>>>(GEMM_ARGS);
+        hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_kernel<1, EPI_VOCAB>), grid, dim3(256), 0, s, st.start, st.stop, 0, GEMM_ARGS);
     else if (plan.nt == 3)
-        gemm_kernel<3, EPI_PARTIAL><<<grid, 256, 0, s>>>(GEMM_ARGS);
+        hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_kernel<3, EPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, GEMM_ARGS);
     else if (plan.nt == 2)
-        gemm_kernel<2, EPI_PARTIAL><<<grid, 256, 0, s>>>(GEMM_ARGS);
+        hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_kernel<2, EPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, GEMM_ARGS);
     else
-        gemm_kernel<1, EPI_PARTIAL><<<grid, 256, 0, s>>>(GEMM_ARGS);
+        hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_kernel<1, EPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, GEMM_ARGS);
 #undef GEMM_ARGS
 }
 

@@ -10,6 +10,7 @@
 // weights stream L2 -> registers in a ring of three chunks.  A workgroup walks its (column group, row group) tiles
 // with the grid's stride.
 #include "bb_internal.h"
+#include <hip/hip_ext.h>
 #include <type_traits>
 #include <algorithm>
 
@@ -318,17 +319,17 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
 }
 
 void launch_gemm_wide(const u32x4* Wt, const float* wscale, const u32x4* Apk, float* P, int mt_total, int N, int K,
-                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out) {
+                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out, LaunchStamps st) {
     const int n_tiles = N / 32, total_chunks = (K + 63) / 64, m_groups = (mt_total + MT - 1) / MT;
     const size_t split_stride = (size_t)mt_total * 32 * N;
     const int nt = plan.nt;
     const int tiles_x = (n_tiles + 4 * nt - 1) / (4 * nt);
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
 #define WARGS Wt, wscale, Apk, P, split_stride, N, mt_total, n_tiles, total_chunks, plan.chunks_per_split, tiles_x, m_groups, swiglu_out
-    if (swiglu_out) gemm_wide_kernel<2, WEPI_SWIGLU><<<grid, 256, 0, s>>>(WARGS);
-    else if (nt == 3) gemm_wide_kernel<3, WEPI_PARTIAL><<<grid, 256, 0, s>>>(WARGS);
-    else if (nt == 2) gemm_wide_kernel<2, WEPI_PARTIAL><<<grid, 256, 0, s>>>(WARGS);
-    else gemm_wide_kernel<1, WEPI_PARTIAL><<<grid, 256, 0, s>>>(WARGS);
+    if (swiglu_out) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<2, WEPI_SWIGLU>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
+    else if (nt == 3) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<3, WEPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
+    else if (nt == 2) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<2, WEPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
+    else hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<1, WEPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
 #undef WARGS
 }
 
