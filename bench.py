@@ -53,7 +53,7 @@ def make_context(w, torch):
     step_rows = w.n_requests * sum(min(b, w.gen_len) for b in w.block_sizes)
     bb = BlockBatch(m, w.decode, Limits(w.n_requests, len(w.block_sizes), L, w.gen_len, step_rows))
     bb.load_weights(gen_weights(m, w.seed, device="cuda:0"))
-    if os.environ.get("BB_WIDE_FORMAT", "1") == "0":
+    if os.environ.get("BB_WIDE_FORMAT", "1") == "0":       # measurements: two bf16 activation terms in every GEMM
         bb.wide_format(False)
     torch.cuda.empty_cache()
     return bb, step_rows
@@ -113,8 +113,7 @@ def steady_state(bb, w, ids, steps, warmup, profile_steps, torch):
     per_step = {k: v["total_ms"] / profile_steps for k, v in prof.items()}
     per_step_corr = {k: (v["total_ms"] - ev_ms * v["launches"]) / profile_steps for k, v in prof.items()}
     hbm_bound = g is prof["gemm_skinny"]
-    packed_rows = w.n_requests * sum(min(b, w.gen_len) for b in w.block_sizes)
-    work = 2.0 if packed_rows <= 128 else 1.5
+    work = 2.0 if os.environ.get("BB_WIDE_FORMAT", "1") == "0" else 1.5
     traffic, commit = stored_gemm_traffic(w.name)
     gbs = g["bytes"] / 1e9 / (raw_ms / 1e3)
     tfl = g["flops"] / 1e12 / (raw_ms / 1e3)
@@ -130,8 +129,8 @@ def steady_state(bb, w, ids, steps, warmup, profile_steps, torch):
             "frac_event_corrected": (g["bytes"] / 1e9 / (corr_ms / 1e3) / HBM_PEAK_GBS) if hbm_bound
             else (g["flops"] / 1e12 / (corr_ms / 1e3) / MFMA_BF16_PEAK_TFLOPS),
             "hbm_gbs": gbs, "mfma_tflops_nominal": tfl, "mfma_work_factor": work, "mfma_tflops_issued": work * tfl,
-            "note": "nominal flops 2*M*N*K; issued = matrix-pipe work in bf16-MFMA equivalents: x2 with two bf16 activation "
-                    "terms (up to 128 packed rows), x1.5 with the fp16 + double-rate fp8 terms of the wide format (more rows)"}
+            "note": "nominal flops 2*M*N*K; issued = matrix-pipe work in bf16-MFMA equivalents: x1.5 with the fp16 + double-rate "
+                    "fp8 terms of the layer GEMMs (x2 for the LM head, which keeps two bf16 activation terms)"}
     # attention of the block forward: K and V of every active branch row are streamed once per layer.  Algorithmic
     # bytes = 2 B per cached element (n_kv_heads * head_dim keys + as many values per token); the cache holds two
     # fp16 terms per element, so the kernel actually streams twice that.
@@ -281,7 +280,7 @@ def main():
         "metric": "branch-batched denoise steps/s (free-running, refreshes included), LLaDA-8B shape, 1 MI355X",
         "value": args.steps / dt, "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights x two-term activations (bf16 hi+lo up to 128 packed rows, fp16 + fp8 remainder beyond), fp32 accumulate",
+        "dtype": "bf16 weights x two-term activations (fp16 + fp8 remainder in the layer GEMMs, bf16 hi+lo in the LM head), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": w.name, "model_shape": m.name, "requests": w.n_requests, "prompt_len": list(w.prompt_lens),
                    "gen_len": w.gen_len, "block_sizes": list(w.block_sizes), "packed_rows": step_rows,

@@ -241,7 +241,7 @@ int bb_debug_gemm(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, floa
  * accuracy per product instead of 2^-17). */
 int bb_debug_gemm_wide(bb_ctx* ctx, const float* A_host, const uint16_t* W_host, float* C_host,
                        int M, int N, int K, int split_k);
-/* Tests and measurements: on == 0 makes passes with more than 128 rows use two bf16 activation terms as well
+/* Tests and measurements: on == 0 makes the layer GEMMs use two bf16 activation terms like the LM head
  * (the default, on != 0, is the fp16 + fp8 operand format for them). */
 int bb_debug_wide_format(bb_ctx* ctx, int on);
 

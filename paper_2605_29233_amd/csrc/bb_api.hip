@@ -41,7 +41,7 @@ struct bb_ctx {
     char* d_stats;                      // device staging for stats copies
     std::string err;
     int last_forward_rows, last_lm_cap;
-    int wide_off;                       // tests: passes with many rows also use two bf16 terms (bb_debug_wide_format)
+    int wide_off;                       // tests: the layer GEMMs use two bf16 terms like the LM head (bb_debug_wide_format)
     int keep_logits;                    // tests: the LM head also stores its fp32 logits (bb_debug_keep_logits)
     // per-launch event timing (bb_profile_*)
     int prof_on;
@@ -96,12 +96,14 @@ struct Bump {
     }
 };
 
-// Passes over more rows than BB_SKINNY_ROWS count as bound by the matrix pipes in the profile classes.  The layer
-// GEMMs take the wide format as soon as there is more than one group of 128 rows: from then on every weight panel is
-// multiplied with two activation panels and the matrix work, not the weight stream, sets the time (measured: 9 %
-// faster at 240 rows, 5-10 % slower at 120 rows, where the two-term kernel's streaming loads win).
+// Passes over more rows than BB_SKINNY_ROWS count as bound by the matrix pipes in the profile classes.
+// The layer GEMMs of every pass take the wide format (fp16 + fp8 operands): with more than one group of 128 rows the
+// matrix work sets the time and three quarters of it is 9-25 % faster; with one group the kernel streams the weights as
+// fast as the two-term kernel in isolation and 6 % faster in the forward, where the chip's clock follows the matrix
+// load.  The LM head keeps two bf16 terms (vocabulary reduction in the epilogue of that kernel).
+// Up to BB_DEFER_ROWS rows the RMSNorm scale is applied after the projection (residual_pack_kernel).
 #define BB_SKINNY_ROWS 256
-#define BB_WIDE_FORMAT_ROWS 128
+#define BB_DEFER_ROWS 128
 
 // Largest split-K output over every row count the forward may be called with.
 static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
@@ -110,7 +112,7 @@ static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
         GemmPlan p = gemm_plan(rows, N, K, 0, rows > 128 ? forced_nt_wide : 0);
         size_t e = (size_t)p.split_k * rows * N;
         if (e > best) best = e;
-        if (rows > BB_WIDE_FORMAT_ROWS) {   // wide-format kernel: the plan's own tile width, or two tiles for gate/up
+        if (rows > BB_DEFER_ROWS) {         // gate/up with the fused SwiGLU epilogue: two tiles per wave
             p = gemm_plan(rows, N, K, 0, forced_nt_wide);
             e = (size_t)p.split_k * rows * N;
             if (e > best) best = e;
@@ -202,7 +204,7 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     // split-KV partial results of block-step attention: up to 8 splits of every 32-row tile
     c->attn_part_elems = ((size_t)l.max_step_rows * (m.n_q_heads / m.n_kv_heads) / 32 + nbr) * m.n_kv_heads * 8 * (64 + 32 * m.head_dim);
     c->attn_part = b.take<float>(c->attn_part_elems);
-    c->ssq = b.take<float>((size_t)(BB_WIDE_FORMAT_ROWS + 31) / 32 * 32 * ((m.d_model + 2047) / 2048));     // block sums of squares of the rows of a block step
+    c->ssq = b.take<float>((size_t)(BB_DEFER_ROWS + 31) / 32 * 32 * ((m.d_model + 2047) / 2048));     // block sums of squares of the rows of a block step
     c->dbg_bytes = 2 * (size_t)lpad * m.n_kv_heads * m.head_dim * sizeof(float);
     c->dbg = b.take<float>(c->dbg_bytes / sizeof(float));
     size_t biggest = (size_t)m.vocab * m.d_model;
@@ -465,29 +467,25 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     const int gk = rows_cap <= BB_SKINNY_ROWS ? BB_K_GEMM_SKINNY : BB_K_GEMM_WIDE;
     // many rows: the layer GEMMs are bound by the matrix pipes and run in the wide format (every kernel that writes
     // a panel for them is told so); the LM head keeps two bf16 terms (its rows are the masked ones only)
-    const int wide = rows_cap > BB_WIDE_FORMAT_ROWS && !c->wide_off;
-    const bool defer = rows_cap <= BB_WIDE_FORMAT_ROWS;     // block steps of at most 128 rows: every gate/up GEMM has a k split, its consumer is the SwiGLU kernel
+    const int wide = !c->wide_off;
+    const bool defer = rows_cap <= BB_DEFER_ROWS;     // block steps of at most 128 rows: every gate/up GEMM has a k split, its consumer is the SwiGLU kernel
     // kind: 0 LM head, 1 O/down, 2 gate/up, 3 QKV (index of the tuning overrides)
     // swiglu_out: where the gate/up projection may put SiLU(gate) * up itself; it does when its k range
     // is not split (then 0 is returned and no partial sums exist)
     auto gemm = [&](int kind, const u32x4* W, const u32x4* Ww, const float* wscale, const u32x4* A, float* P, int N, int K,
                     int rows, int mtt, int klass, u32x4* swiglu_out = nullptr) {
-        if (wide) {
-            // the fused SwiGLU epilogue pairs two tiles per wave; otherwise the plan picks the tile width
-            GemmPlan p = gemm_plan(rows, N, K, 0, swiglu_out ? 2 : 0);
-            const bool fused = swiglu_out && p.split_k == 1 && p.nt == 2;
-            PROF_STAMPED(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-            launch_gemm_wide(Ww, wscale, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr, prof_scope_.stamps());
-            return fused ? 0 : p.split_k;
-        }
-        // with many rows the gate/up projection keeps 256-column tiles: its fused SwiGLU epilogue pairs two tiles per wave
-        const int nt = c->force_nt[kind] > 0 ? c->force_nt[kind] : (swiglu_out && rows > 128 ? 2 : 0);
-        GemmPlan p = gemm_plan(rows, N, K, kind == 0 ? 1 : 0, nt);
-        if (c->force_split[kind] > 0 && kind != 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
-        const bool fused = swiglu_out && !defer && p.split_k == 1 && p.nt == 2;     // (with a deferred norm scale SwiGLU needs the separate kernel)
+        // tile width: the fused SwiGLU epilogue pairs two tiles per wave (passes with more than 128 rows; with fewer the
+        // norm's scale is deferred and SwiGLU needs the separate kernel anyway); otherwise the plan picks it
+        const int nt = c->force_nt[kind] > 0 ? c->force_nt[kind] : (swiglu_out && !defer ? 2 : 0);
+        GemmPlan p = gemm_plan(rows, N, K, 0, nt);
+        if (c->force_split[kind] > 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
+        const bool fused = swiglu_out && !defer && p.split_k == 1 && p.nt == 2;
         PROF_STAMPED(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-        GemmEpilogue epi; epi.swiglu_out = fused ? swiglu_out : nullptr;
-        launch_gemm(W, A, P, mtt, N, K, p, s, epi, prof_scope_.stamps());
+        if (wide) launch_gemm_wide(Ww, wscale, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr, prof_scope_.stamps());
+        else {
+            GemmEpilogue epi; epi.swiglu_out = fused ? swiglu_out : nullptr;
+            launch_gemm(W, A, P, mtt, N, K, p, s, epi, prof_scope_.stamps());
+        }
         return fused ? 0 : p.split_k;
     };
     c->prof_chain = false;              // the first launch records its own start
@@ -501,7 +499,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         const float* ssq = defer ? c->ssq : nullptr;
         int nblk = 0;
         { PROF(BB_K_GLUE, 0, 0);
-          if (defer) nblk = launch_residual_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, c->ssq, s);
+          if (defer) nblk = launch_residual_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, c->ssq, wide, s);
           else launch_rmsnorm_pack(D, c->h, c->part, s_down, pstride, W.g_attn, c->Apk, mt, 0, 0, wide, s); }
         const int s_qkv = gemm(3, W.wqkv, W.wqkv_w, W.s_qkv, c->Apk, c->qkv, nqkv, d, rows_cap, mt, gk);
         { PROF(BB_K_GLUE, 0, 0);
@@ -510,7 +508,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         { PROF(BB_K_ATTENTION, 0, 0); launch_attention(D, c->Q, c->Apk, li, mt, max_seg_rows, seg_base, n_segs, max_pages, c->attn_part, c->attn_part_elems, wide, s); }
         const int s_o = gemm(1, W.wo, W.wo_w, W.s_o, c->Apk, c->part, d, nq, rows_cap, mt, gk);
         { PROF(BB_K_GLUE, 0, 0);
-          if (defer) nblk = launch_residual_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, c->ssq, s);
+          if (defer) nblk = launch_residual_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, c->ssq, wide, s);
           else launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, wide, s); }
         const int s_gu = gemm(2, W.wgu, W.wgu_w, W.s_gu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, c->Apk2);
         if (s_gu > 0) { PROF(BB_K_GLUE, 0, 0);

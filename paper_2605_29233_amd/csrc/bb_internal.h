@@ -235,10 +235,10 @@ void launch_embed(const Dev& D, const uint16_t* emb, float* h, int rows_cap, hip
 // h += sum of split-K partials; out = packed rmsnorm(h) * gain.  gather != 0: rows are the masked (LM-head) rows.
 void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
                          const float* gain, u32x4* Apk, int mt_total, int gather, int bcast, int wide, hipStream_t s);
-// Few rows: h += sum of split-K partials; out = packed h * gain (two bf16 terms) WITHOUT the norm's 1 / rms, whose
+// Few rows: h += sum of split-K partials; out = packed h * gain WITHOUT the norm's 1 / rms, whose
 // ingredients go to ssq[row][block] (returns the blocks per row); the consumers below apply it after the projection.
 int launch_residual_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
-                         const float* gain, u32x4* Apk, int mt_total, float* ssq, hipStream_t s);
+                         const float* gain, u32x4* Apk, int mt_total, float* ssq, int wide, hipStream_t s);
 // q,k,v = sum of partials (* 1 / rms of the row if ssq) + bias; RoPE; q -> Q, k,v -> cache rows (two fp16 terms each)
 void launch_qkv_epilogue(const Dev& D, const float* qkv, int n_partial, size_t partial_stride, const float* bias,
                          half_t* Q, int layer, int rows_cap, const float* ssq, int nblk, hipStream_t s);

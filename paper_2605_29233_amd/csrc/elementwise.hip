@@ -217,19 +217,19 @@ void launch_rmsnorm_pack(const Dev& D, float* h, const float* partial, int n_par
 // Few rows (block steps): the norm's row-wide sum would leave one workgroup per row with the whole row's partial tiles
 // to read, and half the CUs idle.  RMSNorm's scale is one number per row and commutes with the projection that follows:
 // (x / rms(x) * gain) W^T = (x * gain) W^T / rms(x).  So this kernel only adds the split-K partials to the residual,
-// packs x * gain (two bf16 terms) and leaves the sum of squares of each 2048-column block in ssq[row][block]; the kernels
+// packs x * gain (in the panel format asked for) and leaves the sum of squares of each 2048-column block in ssq[row][block]; the kernels
 // that consume the projection (bias + RoPE + cache write, SwiGLU) multiply by 1 / sqrt(sum / d + eps).  One workgroup
 // per (row, block of 2048 columns), one 8-column group per thread.
 #define BB_SSQ_BLOCK 2048
 __global__ __launch_bounds__(256) void residual_pack_kernel(Dev D, float* __restrict__ h, const float* __restrict__ partial,
                                                             int n_partial, size_t partial_stride,
                                                             const float* __restrict__ gain, u32x4* __restrict__ Apk,
-                                                            int mt_total, float* __restrict__ ssq, int nblk) {
+                                                            int mt_total, float* __restrict__ ssq, int nblk, int wide) {
     __shared__ float sh[4];
     const int j = blockIdx.x / nblk, b = blockIdx.x % nblk, d = D.d, k8 = b * (BB_SSQ_BLOCK / 8) + threadIdx.x;
     const bool live = k8 < (d >> 3);
     if (j >= D.counts[0]) {
-        if (live) zero_panel8(Apk, j, k8, mt_total, 0);
+        if (live) zero_panel8(Apk, j, k8, mt_total, wide);
         if (threadIdx.x == 0) ssq[j * nblk + b] = 0.f;
         return;
     }
@@ -252,16 +252,16 @@ __global__ __launch_bounds__(256) void residual_pack_kernel(Dev D, float* __rest
         float y[8];
 #pragma unroll
         for (int q = 0; q < 8; ++q) { ss += v[q] * v[q]; y[q] = v[q] * gg[q]; }
-        store_panel8(Apk, j, k8, mt_total, y, 0);
+        store_panel8(Apk, j, k8, mt_total, y, wide);
     }
     ss = wg_sum(ss, sh);
     if (threadIdx.x == 0) ssq[j * nblk + b] = ss;
 }
 
 int launch_residual_pack(const Dev& D, float* h, const float* partial, int n_partial, size_t partial_stride,
-                         const float* gain, u32x4* Apk, int mt_total, float* ssq, hipStream_t s) {
+                         const float* gain, u32x4* Apk, int mt_total, float* ssq, int wide, hipStream_t s) {
     const int nblk = (D.d + BB_SSQ_BLOCK - 1) / BB_SSQ_BLOCK;
-    residual_pack_kernel<<<mt_total * 32 * nblk, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, ssq, nblk);
+    residual_pack_kernel<<<mt_total * 32 * nblk, 256, 0, s>>>(D, h, partial, n_partial, partial_stride, gain, Apk, mt_total, ssq, nblk, wide);
     return nblk;
 }
 

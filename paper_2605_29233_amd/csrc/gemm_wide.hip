@@ -68,7 +68,7 @@ static __device__ __forceinline__ void to_e4m3x8(const u32x4& w, int& lo, int& h
 //   fp16 k-step 2: MFMAs | LDS reads of step 3 | global loads of chunk c+2's weight fragments 0, 1
 //   fp16 k-step 3: MFMAs | LDS reads of the fp8 fragments | weight fragments 2, 3 | this chunk's weights -> e4m3
 //   fp8 step:      MFMAs | LDS reads of step 0 of chunk c+1
-template <int NT, int EPI>
+template <int NT, int EPI, bool STREAM>
 __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restrict__ Wt, const float* __restrict__ wscale,
                                                            const u32x4* __restrict__ Apk, float* __restrict__ P,
                                                            size_t split_stride, int ldp, int mt_total, int n_tiles,
@@ -77,8 +77,17 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
     static_assert(NT >= 1 && NT <= 3, "one to three weight tiles per wave");
     __shared__ u32x4 lds[3][WCHUNK_U4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int split_id = blockIdx.z;
-    for (int tile = blockIdx.x; tile < tiles_x * tiles_y; tile += gridDim.x) {
+    // STREAM (one row group: every weight line is used once): weight loads carry the non-temporal hint, and with a k
+    // split the (column group, split) items are dealt to the 8 XCDs in contiguous runs in split-major order, so that an
+    // XCD's workgroups share one or two k ranges of the activation panel (as in the two-term kernel).
+    int first_tile = blockIdx.x, split_id = blockIdx.z;
+    if (STREAM && gridDim.z > 1 && tiles_y == 1) {
+        const int n = gridDim.x * gridDim.z, lin = blockIdx.x + gridDim.x * blockIdx.z, e = lin & 7;
+        const int item = e * (n >> 3) + min(e, n & 7) + (lin >> 3);
+        first_tile = item % gridDim.x;
+        split_id = item / gridDim.x;
+    }
+    for (int tile = first_tile; tile < tiles_x * tiles_y; tile += gridDim.x) {
     const int bx = tile % tiles_x, by = tile / tiles_x;
     const int mt0 = by * MT;
     const int mt_cnt = min(MT, mt_total - mt0);
@@ -110,7 +119,10 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
 #pragma unroll
         for (int f = f_lo; f < f_hi; ++f)
 #pragma unroll
-            for (int t = 0; t < NT; ++t) w[f][t] = wbase[t][off + f * 64];     // plain loads: the row groups of an XCD share these lines through its L2
+            for (int t = 0; t < NT; ++t) {
+                if constexpr (STREAM) w[f][t] = __builtin_nontemporal_load(wbase[t] + off + f * 64);
+                else w[f][t] = wbase[t][off + f * 64];      // plain loads: the row groups of an XCD share these lines through its L2
+            }
     };
     auto read_bh = [&](u32x4 (&b)[MT], int stage, int k) {
 #pragma unroll
@@ -326,10 +338,13 @@ void launch_gemm_wide(const u32x4* Wt, const float* wscale, const u32x4* Apk, fl
     const int tiles_x = (n_tiles + 4 * nt - 1) / (4 * nt);
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
 #define WARGS Wt, wscale, Apk, P, split_stride, N, mt_total, n_tiles, total_chunks, plan.chunks_per_split, tiles_x, m_groups, swiglu_out
-    if (swiglu_out) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<2, WEPI_SWIGLU>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
-    else if (nt == 3) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<3, WEPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
-    else if (nt == 2) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<2, WEPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
-    else hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<1, WEPI_PARTIAL>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS);
+#define WLAUNCH(NT_, EPI_, ST_) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<NT_, EPI_, ST_>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS)
+    const bool stream = m_groups == 1;
+    if (swiglu_out) { if (stream) WLAUNCH(2, WEPI_SWIGLU, true); else WLAUNCH(2, WEPI_SWIGLU, false); }
+    else if (nt == 3) { if (stream) WLAUNCH(3, WEPI_PARTIAL, true); else WLAUNCH(3, WEPI_PARTIAL, false); }
+    else if (nt == 2) { if (stream) WLAUNCH(2, WEPI_PARTIAL, true); else WLAUNCH(2, WEPI_PARTIAL, false); }
+    else { if (stream) WLAUNCH(1, WEPI_PARTIAL, true); else WLAUNCH(1, WEPI_PARTIAL, false); }
+#undef WLAUNCH
 #undef WARGS
 }
 

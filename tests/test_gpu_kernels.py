@@ -74,7 +74,11 @@ def test_qkv_projection_gives_the_same_cache_and_logits_under_every_plan(hq, hkv
     """The q|k|v projection of the block forward with tiles of 128, 256 or 384 columns and with k whole or split in
     two (partial tiles summed by the epilogue kernel that applies bias and RoPE and writes q and the K,V cache):
     every plan must give the same cache and logits up to fp32 summation order, for block sizes with and without
-    whole runs of 8 rows, with grouped heads of 64 and 128 dims."""
+    whole runs of 8 rows, with grouped heads of 64 and 128 dims.  The cache entries of layer 0 come straight from the fp32 sums
+    (1e-5 of their scale).  Layer 1's cache and the logits pass through repacked activations: where a different summation
+    order flips the rounding of an activation's fp16 term, its e5m2 remainder (3 significant bits) absorbs the half
+    ulp only to 2^-3, so one element's operand moves by up to 2^-14 of its value; logits of magnitude 10 may
+    therefore differ by a few 1e-4, and the bound below is 1e-4 of the logits' scale."""
     from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT
     from workload.gen import gen_weights, gen_prompt
     shape = ModelShape("qkvtest", 2, 512, hq, hkv, hd, 512, 1024, qkv_bias=bias)
@@ -106,10 +110,12 @@ def test_qkv_projection_gives_the_same_cache_and_logits_under_every_plan(hq, hkv
     for key, (out, kv, X) in results.items():
         assert np.array_equal(X, ref_X), key
         for a, r in zip(out, ref_out):
-            assert a.shape == r.shape and np.abs(a - r).max() <= 2e-4, (key, np.abs(a - r).max())
-        for (K, V), (Kr, Vr) in zip(kv, ref_kv):
-            assert np.abs(K - Kr).max() <= 1e-5 * max(1.0, np.abs(Kr).max()), key
-            assert np.abs(V - Vr).max() <= 1e-5 * max(1.0, np.abs(Vr).max()), key
+            tol = 1e-4 * max(1.0, float(np.abs(r).max()))
+            assert a.shape == r.shape and np.abs(a - r).max() <= tol, (key, np.abs(a - r).max(), tol)
+        for i, ((K, V), (Kr, Vr)) in enumerate(zip(kv, ref_kv)):
+            rel = 1e-5 if i % 2 == 0 else 1e-4          # layer 0: fp32 sums of identical operands; layer 1: repacked operands
+            assert np.abs(K - Kr).max() <= rel * max(1.0, np.abs(Kr).max()), (key, i)
+            assert np.abs(V - Vr).max() <= rel * max(1.0, np.abs(Vr).max()), (key, i)
 
 
 def test_wide_format_forward_agrees_with_two_bf16_terms():
