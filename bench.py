@@ -118,7 +118,8 @@ def steady_state(bb, w, ids, steps, warmup, profile_steps, torch):
     gbs = g["bytes"] / 1e9 / (raw_ms / 1e3)
     tfl = g["flops"] / 1e12 / (raw_ms / 1e3)
     roof = {"bound": "hbm" if hbm_bound else "mfma",
-            "kernel": "gemm_kernel (MFMA GEMM launches of the block forward: %s)" % ("weight streaming" if hbm_bound else "many rows"),
+            "kernel": "gemm_wide_kernel and the LM head's gemm_kernel (MFMA GEMM launches of the block forward: %s)"
+                      % ("weight streaming" if hbm_bound else "many rows"),
             "achieved": gbs if hbm_bound else tfl, "peak": HBM_PEAK_GBS if hbm_bound else MFMA_BF16_PEAK_TFLOPS,
             "unit": "GB/s" if hbm_bound else "TFLOP/s",
             "frac": gbs / HBM_PEAK_GBS if hbm_bound else tfl / MFMA_BF16_PEAK_TFLOPS,
