@@ -109,13 +109,17 @@ struct Bump {
 static size_t buf_elems(int rows_cap, int N, int K, int forced_nt_wide = 0) {
     size_t best = 0;
     for (int rows = 32; rows <= (rows_cap + 31) / 32 * 32; rows += 32) {
-        GemmPlan p = gemm_plan(rows, N, K, 0, rows > 128 ? forced_nt_wide : 0);
-        size_t e = (size_t)p.split_k * rows * N;
-        if (e > best) best = e;
-        if (rows > BB_DEFER_ROWS) {         // gate/up with the fused SwiGLU epilogue: two tiles per wave
-            p = gemm_plan(rows, N, K, 0, forced_nt_wide);
-            e = (size_t)p.split_k * rows * N;
+        // (both operand formats: the wide format can be switched off at run time)
+        for (int variant = 0; variant < 3; ++variant) {
+            auto plan = [&](int nt) { return variant == 0 ? gemm_plan(rows, N, K, 0, nt) : gemm_plan_wide(rows, N, K, 0, nt, variant == 2); };
+            GemmPlan p = plan(rows > 128 ? forced_nt_wide : 0);
+            size_t e = (size_t)p.split_k * rows * N;
             if (e > best) best = e;
+            if (rows > BB_DEFER_ROWS) {         // gate/up with the fused SwiGLU epilogue: two tiles per wave
+                p = plan(forced_nt_wide);
+                e = (size_t)p.split_k * rows * N;
+                if (e > best) best = e;
+            }
         }
     }
     // room for the largest split a tuning override may ask for on a skinny panel
@@ -477,7 +481,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         // tile width: the fused SwiGLU epilogue pairs two tiles per wave (passes with more than 128 rows; with fewer the
         // norm's scale is deferred and SwiGLU needs the separate kernel anyway); otherwise the plan picks it
         const int nt = c->force_nt[kind] > 0 ? c->force_nt[kind] : (swiglu_out && !defer ? 2 : 0);
-        GemmPlan p = gemm_plan(rows, N, K, 0, nt);
+        GemmPlan p = wide ? gemm_plan_wide(rows, N, K, 0, nt, swiglu_out && !defer) : gemm_plan(rows, N, K, 0, nt);
         if (c->force_split[kind] > 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
         const bool fused = swiglu_out && !defer && p.split_k == 1 && p.nt == 2;
         PROF_STAMPED(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
@@ -803,7 +807,7 @@ static int bb_set_kv_impl(bb_ctx* c, int id, int branch, int layer, const float*
 static int bb_debug_gemm_impl(bb_ctx* c, const float* A, const uint16_t* W, float* C, int M, int N, int K, int split_k, int wide) {
     if (!c || !A || !W || !C || M < 1 || N < 32 || K < 16 || N % 32 || K % 16 || split_k < 0 || split_k > BB_MAX_SPLITK) return BB_EINVAL;
     const int mt = (M + 31) / 32, rows_pad = mt * 32;
-    GemmPlan p = gemm_plan(M, N, K, split_k, 0);
+    GemmPlan p = wide ? gemm_plan_wide(M, N, K, split_k, 0) : gemm_plan(M, N, K, split_k, 0);
     // carve private buffers out of the activation region [h, emb): nothing else runs meanwhile
     Bump b{(char*)c->h, 0};
     float* dA = b.take<float>((size_t)M * K);

@@ -209,8 +209,9 @@ static __device__ __forceinline__ MSI msi_merge(MSI a, MSI b) {
 }
 
 // ---- kernel launchers (each enqueues on `s`) -----------------------------------------------------
-struct GemmPlan { int split_k; int chunks_per_split; int nt; };
+struct GemmPlan { int split_k; int chunks_per_split; int nt; int mt = 4; };      // mt: m-tiles of 32 rows per workgroup
 GemmPlan gemm_plan(int m_rows, int N, int K, int forced_split, int forced_nt);
+GemmPlan gemm_plan_wide(int m_rows, int N, int K, int forced_split, int forced_nt, bool fusable = false);     // wide-format kernel: may take mt = 6
 // Epilogue of launch_gemm: partial tiles P[split][m][n] (default); SiLU(gate) * up as the down projection's panel
 // (swiglu_out, needs nt == 2 and no k split); or the vocabulary reduction of the LM head (vocab_part: per row and
 // column tile one (max, sum, argmax); needs no k split and nt <= 2; P is then written only if keep_logits).

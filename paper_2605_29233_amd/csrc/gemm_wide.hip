@@ -21,16 +21,29 @@ typedef int i32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 #define KC 4                                    // fp16 k-steps (of 16) per chunk = weight fragments per (tile, chunk)
-#define MT 4                                    // m-tiles (of 32 rows) per workgroup
 #define DW 3                                    // weight chunks per wave in the register ring
-#define WCHUNK_U4 (MT * BB_WFRAGS * 64)         // uint4 per staged activation chunk (1536 = 24 KiB)
-#define WA_PER_THREAD (WCHUNK_U4 / 256)
 
 #define SG_MFMA 0x008
 #define SG_VMEM 0x020
 #define SG_DSR 0x100
 #define SG_DSW 0x200
-#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+// One scheduling group per m-tile of a phase: NT MFMAs, then this group's share of the phase's LDS reads, LDS writes
+// and global loads (dealt out as evenly as possible, larger shares first).  The builtin wants constants, hence
+// templates.
+template <int MASK, int N> static __device__ __forceinline__ void sgb() {
+    if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+template <int GROUPS, int TOTAL, int I> constexpr int sg_share() { return TOTAL / GROUPS + (I < TOTAL % GROUPS ? 1 : 0); }
+template <int GROUPS, int NT, int DSR_TOTAL, int DSW_TOTAL, int VMEM_TOTAL, int I = 0>
+static __device__ __forceinline__ void sched_groups() {
+    if constexpr (I < GROUPS) {
+        sgb<SG_MFMA, NT>();
+        sgb<SG_DSR, sg_share<GROUPS, DSR_TOTAL, I>()>();
+        sgb<SG_DSW, sg_share<GROUPS, DSW_TOTAL, I>()>();
+        sgb<SG_VMEM, sg_share<GROUPS, VMEM_TOTAL, I>()>();
+        sched_groups<GROUPS, NT, DSR_TOTAL, DSW_TOTAL, VMEM_TOTAL, I + 1>();
+    }
+}
 
 #define WEPI_PARTIAL 0
 #define WEPI_SWIGLU 1
@@ -68,14 +81,17 @@ static __device__ __forceinline__ void to_e4m3x8(const u32x4& w, int& lo, int& h
 //   fp16 k-step 2: MFMAs | LDS reads of step 3 | global loads of chunk c+2's weight fragments 0, 1
 //   fp16 k-step 3: MFMAs | LDS reads of the fp8 fragments | weight fragments 2, 3 | this chunk's weights -> e4m3
 //   fp8 step:      MFMAs | LDS reads of step 0 of chunk c+1
-template <int NT, int EPI, bool STREAM>
+template <int NT, int EPI, bool STREAM, int MT>
 __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restrict__ Wt, const float* __restrict__ wscale,
                                                            const u32x4* __restrict__ Apk, float* __restrict__ P,
                                                            size_t split_stride, int ldp, int mt_total, int n_tiles,
                                                            int total_chunks, int chunks_per_split, int tiles_x, int tiles_y,
                                                            u32x4* __restrict__ Opk) {
-    static_assert(NT >= 1 && NT <= 3, "one to three weight tiles per wave");
-    __shared__ u32x4 lds[3][WCHUNK_U4];
+    static_assert(NT >= 1 && NT <= 3 && NT * MT <= 12, "one to three weight tiles per wave, at most 12 accumulator tiles");
+    constexpr int WCHUNK_U4 = MT * BB_WFRAGS * 64;          // uint4 per staged activation chunk (6 KiB per m-tile)
+    constexpr int WA_PER_THREAD = WCHUNK_U4 / 256;
+    static_assert(WCHUNK_U4 % 256 == 0, "every thread stages the same number of pieces");
+    __shared__ u32x4 lds[DW][WCHUNK_U4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     // STREAM (one row group: every weight line is used once): weight loads carry the non-temporal hint, and with a k
     // split the (column group, split) items are dealt to the 8 XCDs in contiguous runs in split-major order, so that an
@@ -188,57 +204,28 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
 #pragma unroll
         for (int i = 0; i < WA_PER_THREAD; ++i) lds[st1][i * 256 + threadIdx.x] = a[i];
         mfma_hi(w[u][0], bh[0]);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_DSW, 2);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_DSW, 2);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_DSW, 1);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_DSW, 1);
+        sched_groups<MT, NT, MT, WA_PER_THREAD, 0>();
         // fp16 k-step 1
         read_bh(bh[0], st, 2);
         load_a(a, c + 2);
         mfma_hi(w[u][1], bh[1]);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 2);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 2);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 1);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 1);
+        sched_groups<MT, NT, MT, 0, WA_PER_THREAD>();
         __syncthreads();                    // chunk c+1 is staged; stage (c+2) mod 3 is free again
         // fp16 k-step 2
         read_bh(bh[1], st, 3);
         load_w(w[slot2], c + 2, 0, 2);
         mfma_hi(w[u][2], bh[0]);
-        if constexpr (NT >= 2) {
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 1); SGB(SG_VMEM, 2 * NT - 3);
-        } else {
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 1); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 1); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 1);
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 1);
-        }
+        sched_groups<MT, NT, MT, 0, 2 * NT>();
         // fp16 k-step 3 (and the conversion of this chunk's weights for the fp8 step)
         read_bl(bl, st);
         load_w(w[slot2], c + 2, 2, 4);
         convert_w(w8, w[u]);
         mfma_hi(w[u][3], bh[1]);
-        if constexpr (NT >= 2) {
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 2); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 2); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 2); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, NT); SGB(SG_DSR, 2); SGB(SG_VMEM, 2 * NT - 3);
-        } else {
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 2); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 2); SGB(SG_VMEM, 1);
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 2);
-            SGB(SG_MFMA, 1); SGB(SG_DSR, 2);
-        }
+        sched_groups<MT, NT, 2 * MT, 0, 2 * NT>();
         // fp8 step (reads the first fp16 fragments of the next chunk)
         read_bh(bh[0], st1, 0);
         mfma_lo(w8, bl);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1);
-        SGB(SG_MFMA, NT); SGB(SG_DSR, 1);
+        sched_groups<MT, NT, MT, 0, 0>();
     };
     int c = c0;
     for (; c + DW <= c1; c += DW) {
@@ -330,20 +317,57 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
     }
 }
 
+// Plan of a wide-format GEMM.  Up to 256 rows the two-term kernel's plan (one or two groups of 128 rows, k split so
+// that one round of workgroups covers the chip).  With more rows the candidates (rows per workgroup 128 or 192, tile
+// width 128 / 256 / 384 columns, k split 1..4) are priced from measured launches: the time of one 64-k chunk of a
+// workgroup tile (table below: these launches are bound by what reaches the CUs, so a chunk of the 192 x 256 tile,
+// 68 KiB for 12 accumulator tiles, costs less per accumulator tile than one of the 128 x 256 tile, 56 KiB for 8), a
+// fixed prologue and store per tile, whole rounds of 256 workgroups, and the partial tiles, written here and read by
+// the consumer launch once per k split.  fusable: the caller can take SiLU(gate) * up from the epilogue when nt == 2
+// and k is not split; that candidate has no partial tiles at all.
+GemmPlan gemm_plan_wide(int m_rows, int N, int K, int forced_split, int forced_nt, bool fusable) {
+    const int mt_total = (m_rows + 31) / 32;
+    if (mt_total <= 8 || forced_split > 0) return gemm_plan(m_rows, N, K, forced_split, forced_nt);
+    const int n_tiles = N / 32, total_chunks = (K + 63) / 64;
+    static const double chunk_us[2][3] = {{0.75, 1.17, 1.58}, {0.98, 1.654, 0.0}};       // [mt == 6][nt - 1]
+    const double partial_us = (double)mt_total * 32 * N * 4 * 0.433e-6;     // one copy: written at ~10 TB/s, read at ~3 TB/s
+    GemmPlan best = gemm_plan(m_rows, N, K, 0, forced_nt);
+    double best_t = 1e30;
+    for (int mt = 4; mt <= 6; mt += 2)
+        for (int nt = 1; nt <= 3; ++nt) {
+            if (forced_nt > 0 && nt != forced_nt) continue;
+            if (nt * mt > 12 || (nt > 1 && n_tiles < 4 * nt)) continue;
+            const long base = (long)((n_tiles + 4 * nt - 1) / (4 * nt)) * ((mt_total + mt - 1) / mt);
+            for (int sp = 1; sp <= 4 && sp <= std::max(1, total_chunks / 4); ++sp) {
+                const int cps = (total_chunks + sp - 1) / sp, sp_eff = (total_chunks + cps - 1) / cps;
+                const long rounds = (base * sp_eff + 255) / 256;
+                const bool fused = fusable && nt == 2 && sp_eff == 1;
+                const double t = rounds * (cps * chunk_us[mt == 6][nt - 1] + 6.0) + (fused ? 0.0 : sp_eff * partial_us + 5.0);
+                if (t < best_t) { best_t = t; best.split_k = sp_eff; best.chunks_per_split = cps; best.nt = nt; best.mt = mt; }
+            }
+        }
+    return best;
+}
+
 void launch_gemm_wide(const u32x4* Wt, const float* wscale, const u32x4* Apk, float* P, int mt_total, int N, int K,
                       GemmPlan plan, hipStream_t s, u32x4* swiglu_out, LaunchStamps st) {
-    const int n_tiles = N / 32, total_chunks = (K + 63) / 64, m_groups = (mt_total + MT - 1) / MT;
+    const int n_tiles = N / 32, total_chunks = (K + 63) / 64, m_groups = (mt_total + plan.mt - 1) / plan.mt;
     const size_t split_stride = (size_t)mt_total * 32 * N;
     const int nt = plan.nt;
     const int tiles_x = (n_tiles + 4 * nt - 1) / (4 * nt);
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
 #define WARGS Wt, wscale, Apk, P, split_stride, N, mt_total, n_tiles, total_chunks, plan.chunks_per_split, tiles_x, m_groups, swiglu_out
-#define WLAUNCH(NT_, EPI_, ST_) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<NT_, EPI_, ST_>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS)
-    const bool stream = m_groups == 1;
-    if (swiglu_out) { if (stream) WLAUNCH(2, WEPI_SWIGLU, true); else WLAUNCH(2, WEPI_SWIGLU, false); }
-    else if (nt == 3) { if (stream) WLAUNCH(3, WEPI_PARTIAL, true); else WLAUNCH(3, WEPI_PARTIAL, false); }
-    else if (nt == 2) { if (stream) WLAUNCH(2, WEPI_PARTIAL, true); else WLAUNCH(2, WEPI_PARTIAL, false); }
-    else { if (stream) WLAUNCH(1, WEPI_PARTIAL, true); else WLAUNCH(1, WEPI_PARTIAL, false); }
+#define WLAUNCH(NT_, EPI_, ST_, MT_) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<NT_, EPI_, ST_, MT_>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS)
+    const bool stream = m_groups == 1;                  // (a single row group never takes the 192-row tile)
+    if (plan.mt == 6) {
+        if (swiglu_out) WLAUNCH(2, WEPI_SWIGLU, false, 6);
+        else if (nt == 2) WLAUNCH(2, WEPI_PARTIAL, false, 6);
+        else WLAUNCH(1, WEPI_PARTIAL, false, 6);
+    }
+    else if (swiglu_out) { if (stream) WLAUNCH(2, WEPI_SWIGLU, true, 4); else WLAUNCH(2, WEPI_SWIGLU, false, 4); }
+    else if (nt == 3) { if (stream) WLAUNCH(3, WEPI_PARTIAL, true, 4); else WLAUNCH(3, WEPI_PARTIAL, false, 4); }
+    else if (nt == 2) { if (stream) WLAUNCH(2, WEPI_PARTIAL, true, 4); else WLAUNCH(2, WEPI_PARTIAL, false, 4); }
+    else { if (stream) WLAUNCH(1, WEPI_PARTIAL, true, 4); else WLAUNCH(1, WEPI_PARTIAL, false, 4); }
 #undef WLAUNCH
 #undef WARGS
 }
