@@ -271,6 +271,13 @@ int bb_debug_keep_logits(bb_ctx* ctx, int on);
  * panels of at most 128 rows.  Results are unchanged up to fp32 summation order. */
 int bb_debug_set_gemm_plan(bb_ctx* ctx, int kind, int nt, int split_k);
 
+/* Host-only query (no device is touched): the launch plan the library takes for C[M][N] = A[M][K] W[N][K]^T with
+ * the heuristics on (wide != 0: the fp16 + fp8 operand kernel; fusable != 0: the caller could take SiLU(gate) * up
+ * from the epilogue).  out[0] = k splits, out[1] = 64-k chunks per split, out[2] = weight tiles of 32 rows per wave
+ * (workgroup tile = 128 out[2] columns), out[3] = m-tiles of 32 rows per workgroup, out[4] = workgroups launched.
+ * Returns BB_EINVAL for M < 1, N < 32, K < 16, N % 32, K % 16 or out == NULL. */
+int bb_debug_gemm_plan(int M, int N, int K, int wide, int fusable, int out[5]);
+
 /* Measurement aid: copy `bytes` (a multiple of 16) from src_dev to dst_dev (device pointers, disjoint,
  * 16-byte aligned) on the context's stream with a plain kernel that moves 16 bytes per lane, the access
  * width of the library's kernels.  A known-size reference for scaling hardware traffic counters, whose

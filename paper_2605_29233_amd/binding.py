@@ -64,7 +64,7 @@ def lib_path():
 _LIB = None
 EXPORTS = ("bb_workspace_bytes", "bb_create", "bb_destroy", "bb_last_error", "bb_load_weights", "bb_request_open",
            "bb_request_close", "bb_refresh", "bb_denoise_step", "bb_merge_commit", "bb_get_tokens", "bb_get_stats",
-           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_set_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_debug_gemm_wide", "bb_debug_wide_format", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate", "bb_debug_keep_logits")
+           "bb_get_view", "bb_set_state", "bb_get_kv", "bb_set_kv", "bb_read_device", "bb_synchronize", "bb_debug_gemm", "bb_debug_gemm_wide", "bb_debug_wide_format", "bb_profile_enable", "bb_profile_read", "bb_debug_set_gemm_plan", "bb_debug_gemm_plan", "bb_debug_copy16", "bb_generate", "bb_kv_diag_scratch_bytes", "bb_kv_diagnostics", "bb_gemm_static", "bb_debug_mfma_rate", "bb_debug_keep_logits")
 KERNEL_CLASSES = ("gemm_skinny", "gemm_wide", "attention", "glue", "policy")
 
 
@@ -107,6 +107,7 @@ def load_library():
         lib.bb_debug_gemm.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int]
         lib.bb_debug_gemm_wide.argtypes = lib.bb_debug_gemm.argtypes
         lib.bb_debug_wide_format.argtypes = [C.c_void_p, C.c_int]
+        lib.bb_debug_gemm_plan.argtypes = [C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int)]
         lib.bb_kv_diag_scratch_bytes.restype = C.c_size_t
         lib.bb_kv_diag_scratch_bytes.argtypes = [C.c_void_p, C.c_int]
         lib.bb_kv_diagnostics.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -131,6 +132,16 @@ def gemm_static(A, W_bits, C_out, split_k=0, stream=None):
     st = stream if stream is not None else torch.cuda.current_stream(A.device)
     return load_library().bb_gemm_static(C.c_void_p(A.data_ptr()), C.c_void_p(W_bits.data_ptr()), C.c_void_p(C_out.data_ptr()),
                                          M, N, K, int(split_k), C.c_void_p(st.cuda_stream))
+
+
+def gemm_plan(M, N, K, wide=True, fusable=False):
+    """bb_debug_gemm_plan: dict(split_k, chunks_per_split, nt, mt, workgroups) of the launch the library would take
+    (host-only, no device needed)."""
+    out = (C.c_int * 5)()
+    rc = load_library().bb_debug_gemm_plan(int(M), int(N), int(K), int(wide), int(fusable), out)
+    if rc != 0:
+        raise ValueError(f"bb_debug_gemm_plan({M}, {N}, {K}) -> {rc}")
+    return dict(split_k=out[0], chunks_per_split=out[1], nt=out[2], mt=out[3], workgroups=out[4])
 
 
 class StepView:

@@ -1062,6 +1062,15 @@ extern "C" int bb_debug_gemm_wide(bb_ctx* c, const float* A, const uint16_t* W, 
     BB_GUARD(c, bb_debug_gemm_impl(c, A, W, C, M, N, K, split_k, 1));
 }
 
+extern "C" int bb_debug_gemm_plan(int M, int N, int K, int wide, int fusable, int out[5]) {
+    if (M < 1 || N < 32 || K < 16 || N % 32 || K % 16 || !out) return BB_EINVAL;
+    const GemmPlan p = wide ? gemm_plan_wide(M, N, K, 0, 0, fusable != 0) : gemm_plan(M, N, K, 0, 0);
+    const int mt_total = (M + 31) / 32, n_groups = (N / 32 + 4 * p.nt - 1) / (4 * p.nt), m_groups = (mt_total + p.mt - 1) / p.mt;
+    out[0] = p.split_k; out[1] = p.chunks_per_split; out[2] = p.nt; out[3] = p.mt;
+    out[4] = std::min(n_groups * m_groups, 256) * p.split_k;
+    return BB_OK;
+}
+
 extern "C" int bb_debug_wide_format(bb_ctx* c, int on) {
     if (!c) return BB_EINVAL;
     c->wide_off = !on;

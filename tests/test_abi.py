@@ -89,3 +89,31 @@ def test_static_gemm_rejects_bad_sizes_before_touching_a_device(lib):
     assert f(fake, fake, fake, 8, 4128, 64, 0, None) == -3        # beyond the column limit
     assert f(fake, fake, fake, 8, 2048, 4096, 0, None) == -3      # N * K beyond 4 Mi
     assert f(fake, fake, fake, 8, 64, 64, 5, None) == -3          # k split beyond 4
+
+
+def test_gemm_plans_cover_k_fit_the_chip_and_the_register_file(lib):
+    """Host logic of the launch plans (no device): for every shape the k splits cover all 64-k chunks without an
+    empty split, a workgroup holds at most 12 accumulator tiles (the AGPR budget of the wide kernel), the fused
+    SwiGLU candidate keeps two tiles per wave, a single row group keeps the 128-row tile, and no plan launches more
+    than one workgroup per CU and k split."""
+    shapes = [(n, k) for n in (512, 4096, 4608, 12288, 24576, 37888) for k in (512, 3584, 4096, 12288, 18944)]
+    for wide in (False, True):
+        for M in (1, 32, 120, 128, 129, 252, 256, 257, 300, 768, 1920, 3072, 4608, 20480):
+            for N, K in shapes:
+                for fusable in (False, True):
+                    p = binding.gemm_plan(M, N, K, wide, fusable)
+                    chunks = (K + 63) // 64
+                    assert 1 <= p["split_k"] <= 16 and p["nt"] in (1, 2, 3) and p["mt"] in (4, 6), (M, N, K, p)
+                    assert p["split_k"] * p["chunks_per_split"] >= chunks > (p["split_k"] - 1) * p["chunks_per_split"], (M, N, K, p)
+                    assert p["nt"] * p["mt"] <= 12, (M, N, K, p)
+                    assert p["workgroups"] <= 256 * p["split_k"], (M, N, K, p)
+                    if not wide or M <= 256:
+                        assert p["mt"] == 4, (M, N, K, p)
+    # the shapes the fused SwiGLU epilogue is used on: gate/up of the refresh and of the 16-request step
+    for M in (768, 1920, 3072):
+        p = binding.gemm_plan(M, 24576, 4096, True, True)
+        assert p["nt"] == 2 and p["split_k"] == 1, p
+    with pytest.raises(ValueError):
+        binding.gemm_plan(0, 4096, 4096)
+    with pytest.raises(ValueError):
+        binding.gemm_plan(64, 4100, 4096)
