@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
 
 // Plan of a wide-format GEMM.  Up to 256 rows the two-term kernel's plan (one or two groups of 128 rows, k split so
 // that one round of workgroups covers the chip).  With more rows the candidates (rows per workgroup 128 or 192, tile
-// width 128 / 256 / 384 columns, k split 1..4) are priced from measured launches: the time of one 64-k chunk of a
+// width 128 / 256 / 384 columns, k split) are priced from measured launches: the time of one 64-k chunk of a
 // workgroup tile (table below: these launches are bound by what reaches the CUs, so a chunk of the 192 x 256 tile,
 // 68 KiB for 12 accumulator tiles, costs less per accumulator tile than one of the 128 x 256 tile, 56 KiB for 8), a
 // fixed prologue and store per tile, whole rounds of 256 workgroups, and the partial tiles, written here and read by
@@ -338,7 +338,7 @@ GemmPlan gemm_plan_wide(int m_rows, int N, int K, int forced_split, int forced_n
             if (forced_nt > 0 && nt != forced_nt) continue;
             if (nt * mt > 12 || (nt > 1 && n_tiles < 4 * nt)) continue;
             const long base = (long)((n_tiles + 4 * nt - 1) / (4 * nt)) * ((mt_total + mt - 1) / mt);
-            for (int sp = 1; sp <= 4 && sp <= std::max(1, total_chunks / 4); ++sp) {
+            for (int sp = 1; sp <= BB_MAX_SPLITK && sp <= std::max(1, total_chunks / 4); ++sp) {
                 const int cps = (total_chunks + sp - 1) / sp, sp_eff = (total_chunks + cps - 1) / cps;
                 const long rounds = (base * sp_eff + 255) / 256;
                 const bool fused = fusable && nt == 2 && sp_eff == 1;

@@ -50,6 +50,9 @@ def test_mfma_gemm_matches_fp64(bb, M, N, K, split):
 @pytest.mark.parametrize("M,N,K,split", [
     (32, 32, 16, 1), (1, 64, 32, 1), (56, 768, 256, 0), (37, 256, 688, 0), (130, 1024, 256, 0),
     (300, 96, 4096, 7), (384, 1376, 256, 0), (700, 4608, 512, 0), (1536, 5632, 128, 0), (3000, 512, 2752, 2),
+    # shapes whose plan takes the 192-row workgroup tile: two tiles per wave with a ragged last row group; one tile
+    # per wave with k split in two; one tile per wave with a number of column tiles that is no multiple of four
+    (3000, 4096, 1024, 0), (740, 4096, 4096, 0), (1100, 4192, 768, 0),
 ])
 def test_wide_format_gemm_matches_fp64(bb, M, N, K, split):
     """The fp16 + fp8 operand kernel of the passes with many rows: activation = fp16 term + e5m2 remainder,
@@ -60,6 +63,9 @@ def test_wide_format_gemm_matches_fp64(bb, M, N, K, split):
     Wb = gen_normal_bf16(1, f"w{N}x{K}", N * K, 0.05).view(torch.int16).numpy().view(np.uint16).reshape(N, K).copy()
     Wb[0::7] = ((Wb[0::7].astype(np.uint32) << 16).view(np.float32) * 2.0 ** -12).view(np.uint32) >> 16   # some tiny rows
     W = (Wb.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    from paper_2605_29233_amd.binding import gemm_plan
+    if (M, N, K) in ((3000, 4096, 1024), (740, 4096, 4096), (1100, 4192, 768)):
+        assert gemm_plan(M, N, K, wide=True)["mt"] == 6, "this case is here for the 192-row tile"
     print(f"wide gemm case M={M} N={N} K={K} split={split}", flush=True)
     C = bb.debug_gemm(A, Wb, split, wide=True)
     ref = A.astype(np.float64) @ W.T
