@@ -187,6 +187,9 @@ static void layout(bb_ctx* c, char* base, size_t* total) {
     D.copies = b.take<PageCopy>((size_t)nbr * D.n_pages);
     D.req_list = b.take<int>(l.max_requests);
     D.req_flags = b.take<int>(l.max_requests);
+    D.commit_skip = b.take<int>(l.max_requests);
+    D.merge_p = b.take<float>((size_t)nbr * l.max_branches * D.gmax);
+    D.merge_x0 = b.take<int>((size_t)nbr * D.gmax);
     c->d_stats = b.take<char>(sizeof(ReqHeader) + sizeof(bb_branch_state) * BB_MAX_BRANCHES);
     D.Kc = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);
     D.Vt = b.take<half_t>((size_t)m.n_layers * phys_rows * lpad * m.n_kv_heads * m.head_dim * 2);

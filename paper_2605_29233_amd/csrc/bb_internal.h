@@ -62,6 +62,9 @@ struct Dev {
     PageCopy* copies;           // [max_req*max_br*n_pages]
     int* req_list;              // [max_req] request slots of the current call
     int* req_flags;             // [max_req] per listed request after a commit: bit 0 finished, bit 1 refresh due; bits 8.. forwards until a refresh is due
+    int* commit_skip;           // [max_req] per listed request: the commit ended the request before MergeSync (EOS winner)
+    float* merge_p;             // [max_req][max_br d][max_br s][gmax] P_d(i, token of row s at i) as of the start of MergeSync
+    int* merge_x0;              // [max_req][max_br][gmax] the rows' generation tokens at the start of MergeSync
 };
 
 static inline __host__ __device__ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }

@@ -189,7 +189,6 @@ __global__ __launch_bounds__(256) void page_copy_kernel(Dev D) {
 
 void launch_page_copies(const Dev& D, hipStream_t s) { page_copy_kernel<<<1024, 256, 0, s>>>(D); }
 
-__global__ void zero_copy_count_kernel(Dev D) { D.counts[2] = 0; }
 
 // ---- commit / merge / sync ----------------------------------------------------------------------
 struct CommitShared {
@@ -239,7 +238,72 @@ static __device__ float prob_of(const Dev& D, const u32x4* lm, const float* hf, 
     return expf(acc - lse);
 }
 
-__global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* __restrict__ lm) {
+// prob_of by one thread, with the wave's order of additions (64 strided partial sums, then the pairwise tree as lane 0
+// sees it): the same bits.  Only for a lookup that finds no row (see merge_prob).
+static __device__ float prob_of_serial(const Dev& D, const u32x4* lm, const float* hf, float lse, int v) {
+    const int k8s = D.d >> 3;
+    float part[64];
+    for (int lane = 0; lane < 64; ++lane) {
+        float acc = 0.f;
+        for (int k8 = lane; k8 < k8s; k8 += 64) {
+            const u32x4 w = lm[tileW_u4(v, k8, k8s >> 1)];
+            const uint16_t* wb = reinterpret_cast<const uint16_t*>(&w);
+            const float* x = hf + k8 * 8;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) acc += x[q] * bf16_to_f32(wb[q]);
+        }
+        part[lane] = acc;
+    }
+    for (int o = 32; o > 0; o >>= 1)
+        for (int lane = 0; lane < o; ++lane) part[lane] += part[lane + o];
+    return expf(part[0] - lse);
+}
+
+// MergeSync asks for P_d(i, v) only where destination row d holds a mask at i and v is the token some other row
+// holds there.  Rows change during MergeSync only by taking such tokens, and a destination is written only in its
+// own turn, so every probability the sequential pass can ask for is P_d(i, token of row s at i) for the rows as they
+// stand when MergeSync starts.  This kernel computes them all at once, one wave per (d, s, i) with d masked and s
+// not (grid = 16 positions x ordered pair (d, s) x listed request), and the diagonal pairs keep the rows' tokens:
+// the pass then looks a probability up by its token.  Same dot product as before, so the same bits.
+__global__ __launch_bounds__(256) void merge_probs_kernel(Dev D, const u32x4* __restrict__ lm) {
+    if (D.commit_skip[blockIdx.z]) return;
+    const int slot = D.req_list[blockIdx.z];
+    const ReqHeader& H = D.hdr[slot];
+    const int d = blockIdx.y / D.max_br, s = blockIdx.y % D.max_br;
+    if (d >= H.N || s >= H.N) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, L_p = H.L_p, G = H.L - H.L_p;
+    const int* Xd = D.X + ((size_t)slot * D.max_br + d) * D.lpad;
+    const int* Xs = D.X + ((size_t)slot * D.max_br + s) * D.lpad;
+    for (int q = 0; q < 4; ++q) {
+        const int j = blockIdx.x * 16 + wave * 4 + q;
+        if (j >= G) break;
+        if (s == d) {
+            if (lane == 0) D.merge_x0[((size_t)slot * D.max_br + d) * D.gmax + j] = Xd[L_p + j];
+            continue;
+        }
+        const int v = Xs[L_p + j];
+        if (Xd[L_p + j] != D.mask_id || v == D.mask_id) continue;
+        const size_t mi = ((size_t)slot * D.max_br + d) * D.gmax + j;
+        const float p = prob_of(D, lm, D.map_hf + mi * D.d, D.map_lse[mi], v);
+        if (lane == 0) D.merge_p[(((size_t)slot * D.max_br + d) * D.max_br + s) * D.gmax + j] = p;
+    }
+}
+
+// P_d(i, v), j = i - L_p, from the table of merge_probs_kernel: row s held v at the start unless it took it from
+// another row since; then that row (or the one it took it from) held it.  Computed directly if no row did.
+static __device__ float merge_prob(const Dev& D, const u32x4* lm, int slot, int N, int d, int s, int j, int v) {
+    const int* x0 = D.merge_x0 + (size_t)slot * D.max_br * D.gmax + j;
+    const float* T = D.merge_p + ((size_t)slot * D.max_br + d) * D.max_br * D.gmax + j;
+    if (x0[(size_t)s * D.gmax] == v) return T[(size_t)s * D.gmax];
+    for (int q = 0; q < N; ++q)
+        if (q != d && x0[(size_t)q * D.gmax] == v) return T[(size_t)q * D.gmax];
+    const size_t mi = ((size_t)slot * D.max_br + d) * D.gmax + j;
+    return prob_of_serial(D, lm, D.map_hf + mi * D.d, D.map_lse[mi], v);
+}
+
+// phase 0: DecodeCurrentBlock, CheckEOS, AdvanceCompletedBlocks; phase 1 (after merge_probs_kernel): MergeSync and
+// the end of the step.
+__global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* __restrict__ lm, int phase) {
     __shared__ CommitShared S;
     const int slot = D.req_list[blockIdx.x], t = threadIdx.x;
     ReqHeader& H = D.hdr[slot];
@@ -248,6 +312,8 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
     int* X = D.X + (size_t)slot * D.max_br * D.lpad;
     const size_t map0 = (size_t)slot * D.max_br * D.gmax;
 
+    if (phase == 0) {
+    if (t == 0) { D.commit_skip[blockIdx.x] = 0; if (blockIdx.x == 0) D.counts[2] = 0; }    // (the copy list is filled in phase 1)
     // -- DecodeCurrentBlock (Eq. 1) for every branch that received logits ---------------------
     for (int k = 0; k < N; ++k) {
         __syncthreads();
@@ -315,7 +381,10 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
                 if (t == 0) { B[k].tokens_decoded = c; B[k].done = 1; B[k].start = B[k].end = L; }
             }
             if (t < BB_MAX_BRANCHES) H.pending[t] = 0;
-            if (t == 0) { H.finished = 2; H.winner = S.win; H.eos_pos = S.win_eos; H.all_done = 1; H.refresh_due = 0; D.req_flags[blockIdx.x] = 1; }
+            if (t == 0) {
+                H.finished = 2; H.winner = S.win; H.eos_pos = S.win_eos; H.all_done = 1; H.refresh_due = 0; D.req_flags[blockIdx.x] = 1;
+                D.commit_skip[blockIdx.x] = 1;
+            }
             return;
         }
     }
@@ -323,6 +392,9 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
     if (t < BB_MAX_BRANCHES) H.pending[t] = 0;
     // -- AdvanceCompletedBlocks ----------------------------------------------------------------
     for (int k = 0; k < N; ++k) advance(D, &B[k], X + (size_t)k * D.lpad, L, S.si);
+    return;
+    }
+    if (D.commit_skip[blockIdx.x]) return;
     // -- MergeSync (Alg. 2) ---------------------------------------------------------------------
     for (int k = 0; k < N; ++k) {
         const int c = count_decoded(D, X + (size_t)k * D.lpad, L_p, L, S.si);
@@ -359,41 +431,48 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
             __syncthreads();
             if (B[d].done) continue;
             int* Xd = X + (size_t)d * D.lpad;
-            // CompatibleSources, evaluated once for this destination
+            // CompatibleSources, evaluated once for this destination: conflicts with every source counted in one pass
+            // (conflicts are rare, so the shared counters are rarely touched; prompt rows are equal)
+            if (t < BB_MAX_BRANCHES) S.compat[t] = 0;
+            if (t == 0) S.merged = 0;
+            __syncthreads();
+            for (int i = L_p + t; i < L; i += 256) {
+                const int xd = Xd[i];
+                if (xd == mask) continue;
+                for (int oj = 0; oj < n_order; ++oj) {
+                    const int s = S.order[oj];
+                    if (s == d) continue;
+                    const int xs = X[(size_t)s * D.lpad + i];
+                    if (xs != mask && xs != xd) atomicAdd(&S.compat[s], 1);
+                }
+            }
+            __syncthreads();
+            // (until the next destination S.compat[s] holds the number of conflicts: compatible = none, and not d itself)
             int lo = L, hi = 0;
             for (int oj = 0; oj < n_order; ++oj) {
                 const int s = S.order[oj];
-                if (s == d) { if (t == 0) S.compat[s] = 0; continue; }
-                const int* Xs = X + (size_t)s * D.lpad;
-                int bad = 0;
-                for (int i = L_p + t; i < L; i += 256) bad += Xs[i] != mask && Xd[i] != mask && Xs[i] != Xd[i];   // prompt rows are equal
-                bad = wg_sum_i(bad, S.si);
-                if (t == 0) S.compat[s] = bad == 0;
-                if (bad == 0) { lo = min(lo, B[s].start); hi = max(hi, B[s].end); }
+                if (s != d && S.compat[s] == 0) { lo = min(lo, B[s].start); hi = max(hi, B[s].end); }
             }
-            if (t == 0) S.merged = 0;
-            __syncthreads();
-            // positions of the union of the sources' windows, one wave per position
-            for (int i = lo + (t >> 6); i < hi; i += 4) {
+            // positions of the union of the sources' windows, one thread per position
+            for (int i = lo + t; i < hi; i += 256) {
                 if (Xd[i] != mask) continue;
                 float best_p = -1.f; int best_v = -1;
-                const size_t mi = map0 + (size_t)d * D.gmax + (i - L_p);
                 for (int oj = 0; oj < n_order; ++oj) {
                     const int s = S.order[oj];
-                    if (s == d || !S.compat[s] || i < B[s].start || i >= B[s].end) continue;   // in the union at all?
+                    if (s == d || S.compat[s] != 0 || i < B[s].start || i >= B[s].end) continue;   // in the union at all?
                     best_v = -2; break;
                 }
                 if (best_v != -2) continue;
                 best_v = -1;
                 for (int oj = 0; oj < n_order; ++oj) {
                     const int s = S.order[oj];
-                    if (s == d || !S.compat[s]) continue;
+                    if (s == d || S.compat[s] != 0) continue;
                     const int v = X[(size_t)s * D.lpad + i];
                     if (v == mask) continue;
-                    const float p = prob_of(D, lm, D.map_hf + mi * D.d, D.map_lse[mi], v);
+                    const float p = merge_prob(D, lm, slot, N, d, s, i - L_p, v);
                     if (p > best_p) { best_p = p; best_v = v; }      // strict: earliest source keeps a tie
                 }
-                if (best_v >= 0 && best_p > D.tau_merge && (t & 63) == 0) { Xd[i] = best_v; atomicAdd(&S.merged, 1); }
+                if (best_v >= 0 && best_p > D.tau_merge) { Xd[i] = best_v; atomicAdd(&S.merged, 1); }
             }
             __syncthreads();
             if (t == 0) B[d].tokens_merged += S.merged;
@@ -474,8 +553,10 @@ __global__ __launch_bounds__(256) void commit_merge_kernel(Dev D, const u32x4* _
 }
 
 void launch_commit_merge(const Dev& D, int n_req, const uint16_t* lm_head, hipStream_t s) {
-    zero_copy_count_kernel<<<1, 1, 0, s>>>(D);
-    commit_merge_kernel<<<n_req, 256, 0, s>>>(D, reinterpret_cast<const u32x4*>(lm_head));
+    const u32x4* lm = reinterpret_cast<const u32x4*>(lm_head);
+    commit_merge_kernel<<<n_req, 256, 0, s>>>(D, lm, 0);
+    merge_probs_kernel<<<dim3((D.gmax + 15) / 16, D.max_br * D.max_br, n_req), 256, 0, s>>>(D, lm);
+    commit_merge_kernel<<<n_req, 256, 0, s>>>(D, lm, 1);
     page_copy_kernel<<<1024, 256, 0, s>>>(D);
 }
 
