@@ -222,54 +222,77 @@ def main():
     steady["roofline"]["issued_mfma_frac_of_measured_rate"] = steady["roofline"]["mfma_tflops_issued"] / mfma_tflops
 
     # ---- 4. free-running decode: the timed region ---------------------------------------------------
-    # Every timed step is a real block forward: the per-request flags are read back after each commit (one
-    # small copy; the launches of the next step still run ahead of the GPU), a refresh runs when a request
-    # says it is due, and a request that has finished is closed and opened again (its initial full forward
-    # and first commit then fall inside the timed region as extra work, not as a step).
+    # Every timed step is a real block forward.  The loop is the library's own driver loop (bb_generate) written out:
+    # while no listed request can need a refresh, block forwards and commits are enqueued back to back without reading
+    # anything back; then the per-request summaries are read (one synchronisation), a refresh runs for the requests
+    # that say it is due, and a request that has finished is closed and opened again (its initial full forward and
+    # first commit then fall inside the timed region as extra work, not as a step).  Steps are counted from the
+    # device's own forward counters, and the refresh cadence is asserted at every read.
     tally = {"committed": 0, "refresh": 0, "init": 0, "completed": 0}
     prev = {}
+    fwd_at_refresh = {}                 # request -> nfe_block when its cache was last rebuilt
 
     def account(r, st):
         d = sum(st.branch[k].tokens_decoded for k in range(st.n_branches))
         a = prev.get(r, (0, 0))
         tally["committed"] += d - a[0]
         tally["refresh"] += st.nfe_refresh - a[1]
+        fwd_at_refresh.setdefault(r, st.nfe_block)       # a request that was just opened: its initial forward built the cache
         prev[r] = (d, st.nfe_refresh)
 
     def restart(i):
         bb.request_close(ids[i])
+        prev.pop(ids[i], None)
+        fwd_at_refresh.pop(ids[i], None)
         ids[i] = bb.request_open(gen_prompt(m, w.seed, i, w.prompt_lens[i]), w.gen_len, w.block_sizes)
         bb.refresh([ids[i]], BB_INIT)
         st = bb.merge_commit([ids[i]])[0]
         prev.pop(ids[i], None)
+        fwd_at_refresh.pop(ids[i], None)
         tally["init"] += 1
         return st
 
     stats = [restart(i) for i in range(len(ids))]
+    for i, st in enumerate(stats):
+        account(ids[i], st)
 
-    def one_step():
-        due = [r for r, st in zip(ids, stats) if st.refresh_due and not st.finished]
-        if due:
-            bb.refresh(due, BB_PERIODIC)
-        bb.denoise_step(ids, want_view=False)
-        new = bb.merge_commit(ids)
-        for i, st in enumerate(new):
-            account(ids[i], st)
-            if st.finished:
-                tally["completed"] += 1
-                st = restart(i)
+    def run_steps(n_steps):
+        """Runs exactly n_steps batched block forwards (with the refreshes and restarts that fall between them)."""
+        done = 0
+        while done < n_steps:
+            due = [r for r, st in zip(ids, stats) if st.refresh_due and not st.finished]
+            if due:
+                bb.refresh(due, BB_PERIODIC)
+                for r, st in zip(ids, stats):
+                    if r in due:
+                        fwd_at_refresh[r] = st.nfe_block
+            # forwards that may run before any request needs a refresh (a refreshed request has a whole interval)
+            quiet = min(R if r in due else R - (st.nfe_block - fwd_at_refresh[r]) for r, st in zip(ids, stats))
+            assert quiet >= 1, quiet
+            k = min(quiet, 8, n_steps - done)        # (read at least every 8 forwards: one that finishes is then not stepped in vain for long)
+            before = [st.nfe_block for st in stats]
+            for _ in range(k):
+                bb.denoise_step(ids, want_view=False)
+                bb.merge_commit(ids, want_stats=False)
+            new = [bb.get_stats(r) for r in ids]            # (the first of these waits for the stream)
+            done += max(st.nfe_block - b0 for st, b0 in zip(new, before))      # a request that finished on the way ran fewer
+            for i, st in enumerate(new):
                 account(ids[i], st)
-            stats[i] = st
+                since = st.nfe_block - fwd_at_refresh[ids[i]]
+                assert st.finished or (since <= R and bool(st.refresh_due) == (since >= R)), (since, st.refresh_due, R)
+                if st.finished:
+                    tally["completed"] += 1
+                    st = restart(i)
+                    account(ids[i], st)
+                stats[i] = st
 
-    for _ in range(args.warmup):
-        one_step()
+    run_steps(args.warmup)
     for k in tally:
         tally[k] = 0
     bb.synchronize()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
+    run_steps(args.steps)
     bb.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0

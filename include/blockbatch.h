@@ -173,7 +173,7 @@ int bb_merge_commit(bb_ctx* ctx, const int* req_ids_host, int n, bb_request_stat
  * requests still running, until every one has finished (all branches done, or an EOS-ready branch
  * selected) or max_block_forwards batched forwards have run.  The loop reads one flags word per listed
  * request back (a single small copy) only when a refresh may fall due or the forward limit is reached:
- * in between, up to R forwards are enqueued back to back.  stats_out_host: n entries (may be NULL).  The output of
+ * in between, up to min(R, 8) forwards are enqueued back to back.  stats_out_host: n entries (may be NULL).  The output of
  * request i is row stats[i].winner of bb_get_tokens, up to stats[i].eos_pos if that is >= 0.
  * Returns BB_OK also when the forward limit stopped it (finished == 0 then). */
 int bb_generate(bb_ctx* ctx, const int* req_ids_host, int n, int max_block_forwards, bb_request_stats* stats_out_host);

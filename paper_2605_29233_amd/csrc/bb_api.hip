@@ -662,7 +662,8 @@ static int bb_generate_impl(bb_ctx* c, const int* ids, int n, int max_block_forw
         if (!due.empty() && (rc = bb_refresh_impl(c, due.data(), (int)due.size(), BB_PERIODIC)) != BB_OK) return rc;
         // No refresh can fall due during the next `quiet` forwards, so they are enqueued without reading anything
         // back; a request that finishes on the way contributes no rows and counts no forward afterwards.
-        const int k = std::min(quiet, max_block_forwards - fwd);
+        // (and the flags are read at least every 8 forwards, so that a request that has finished is not stepped in vain for long)
+        const int k = std::min(std::min(quiet, 8), max_block_forwards - fwd);
         for (int j = 0; j < k; ++j) {
             if ((rc = bb_denoise_step_impl(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
             if ((rc = bb_merge_commit_impl(c, run.data(), (int)run.size(), nullptr)) != BB_OK) return rc;
