@@ -480,15 +480,18 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
     // swiglu_out: where the gate/up projection may put SiLU(gate) * up itself; it does when its k range
     // is not split (then 0 is returned and no partial sums exist)
     auto gemm = [&](int kind, const u32x4* W, const u32x4* Ww, const float* wscale, const u32x4* A, float* P, int N, int K,
-                    int rows, int mtt, int klass, u32x4* swiglu_out = nullptr) {
-        // tile width: the fused SwiGLU epilogue pairs two tiles per wave (passes with more than 128 rows; with fewer the
-        // norm's scale is deferred and SwiGLU needs the separate kernel anyway); otherwise the plan picks it
+                    int rows, int mtt, int klass, u32x4* swiglu_out = nullptr, const float* ssq = nullptr, int nblk = 0) {
+        // tile width: the fused SwiGLU epilogue pairs two tiles per wave (passes with more than 128 rows); otherwise the
+        // plan picks it.  With at most 128 rows the norm's scale is deferred: the wide-format kernel's SwiGLU epilogue
+        // applies it (ssq) where the plan comes out with two tiles per wave and k whole (many columns: the Dream
+        // shape), the two-term kernel leaves it to the separate SwiGLU kernel.
         const int nt = c->force_nt[kind] > 0 ? c->force_nt[kind] : (swiglu_out && !defer ? 2 : 0);
         GemmPlan p = wide ? gemm_plan_wide(rows, N, K, 0, nt, swiglu_out && !defer) : gemm_plan(rows, N, K, 0, nt);
         if (c->force_split[kind] > 0 && rows <= 128) p = gemm_plan(rows, N, K, c->force_split[kind], c->force_nt[kind]);
-        const bool fused = swiglu_out && !defer && p.split_k == 1 && p.nt == 2;
+        const bool fused = swiglu_out && (wide || !defer) && p.split_k == 1 && p.nt == 2;
         PROF_STAMPED(klass, 2.0 * N * K, 2.0 * rows * (double)N * K);
-        if (wide) launch_gemm_wide(Ww, wscale, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr, prof_scope_.stamps());
+        if (wide) launch_gemm_wide(Ww, wscale, A, P, mtt, N, K, p, s, fused ? swiglu_out : nullptr, prof_scope_.stamps(),
+                                   fused ? ssq : nullptr, nblk, m.rms_eps);
         else {
             GemmEpilogue epi; epi.swiglu_out = fused ? swiglu_out : nullptr;
             launch_gemm(W, A, P, mtt, N, K, p, s, epi, prof_scope_.stamps());
@@ -517,7 +520,7 @@ static int forward(bb_ctx* c, int rows_cap, int lm_cap, int mode, int seg_base, 
         { PROF(BB_K_GLUE, 0, 0);
           if (defer) nblk = launch_residual_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, c->ssq, wide, s);
           else launch_rmsnorm_pack(D, c->h, c->part, s_o, pstride, W.g_ffn, c->Apk, mt, 0, 0, wide, s); }
-        const int s_gu = gemm(2, W.wgu, W.wgu_w, W.s_gu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, c->Apk2);
+        const int s_gu = gemm(2, W.wgu, W.wgu_w, W.s_gu, c->Apk, c->gu, ngu, d, rows_cap, mt, gk, c->Apk2, ssq, nblk);
         if (s_gu > 0) { PROF(BB_K_GLUE, 0, 0);
           launch_swiglu_epilogue(D, c->gu, s_gu, (size_t)rows_pad * ngu, ngu, c->Apk2, rows_cap, mt, wide, ssq, nblk, s); }
         s_down = gemm(1, W.wdown, W.wdown_w, W.s_down, c->Apk2, c->part, d, f, rows_cap, mt, gk);

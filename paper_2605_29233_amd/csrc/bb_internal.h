@@ -227,9 +227,12 @@ void launch_gemm(const u32x4* Wt, const u32x4* Apk, float* P, int mt_total, int 
 void launch_tile_weights(const uint16_t* src, int rows, int K, u32x4* dst, int dst_row0, int interleave, hipStream_t s);
 void launch_pack_rows(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);
 // The same contraction with both operands in the wide format (fp16 + fp8 terms, see above); wscale[n] = 2^-S of weight
-// row n.  plan.nt is capped at 2; swiglu_out as in GemmEpilogue (a wide-format panel).
+// row n.  swiglu_out as in GemmEpilogue (a wide-format panel).  ssq (with swiglu_out): the activation rows carry no
+// RMSNorm scale yet, ssq[row][nblk] holds their sums of squares per block of columns (K = the model dimension) and
+// the SwiGLU epilogue applies 1 / sqrt(sum / K + rms_eps) to gate and up.
 void launch_gemm_wide(const u32x4* Wt, const float* wscale, const u32x4* Apk, float* P, int mt_total, int N, int K,
-                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out = nullptr, LaunchStamps st = LaunchStamps());
+                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out = nullptr, LaunchStamps st = LaunchStamps(),
+                      const float* ssq = nullptr, int nblk = 0, float rms_eps = 0.f);
 void launch_tile_weights_wide(const uint16_t* src, int rows, int K, u32x4* dst, float* scale_out, int dst_row0, int interleave,
                               hipStream_t s);
 void launch_pack_rows_wide(const float* A, int M, int K, u32x4* Apk, int mt_total, hipStream_t s);

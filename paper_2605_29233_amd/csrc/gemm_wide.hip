@@ -86,7 +86,8 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
                                                            const u32x4* __restrict__ Apk, float* __restrict__ P,
                                                            size_t split_stride, int ldp, int mt_total, int n_tiles,
                                                            int total_chunks, int chunks_per_split, int tiles_x, int tiles_y,
-                                                           u32x4* __restrict__ Opk) {
+                                                           u32x4* __restrict__ Opk, const float* __restrict__ ssq, int nblk,
+                                                           float inv_d, float eps) {
     static_assert(NT >= 1 && NT <= 3 && NT * MT <= 12, "one to three weight tiles per wave, at most 12 accumulator tiles");
     constexpr int WCHUNK_U4 = MT * BB_WFRAGS * 64;          // uint4 per staged activation chunk (6 KiB per m-tile)
     constexpr int WA_PER_THREAD = WCHUNK_U4 / 256;
@@ -259,10 +260,19 @@ __global__ __launch_bounds__(256, 1) void gemm_wide_kernel(const u32x4* __restri
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 if (mt >= mt_cnt) break;
+                // ssq: the activation rows were packed without their RMSNorm scale (sums of squares per block of
+                // columns instead); both factors of the product take 1 / rms of this lane's row here
+                float inv = 1.0f;
+                if (ssq) {
+                    const int m = (mt0 + mt) * 32 + (lane & 31);
+                    float t = 0.f;
+                    for (int b = 0; b < nblk; ++b) t += ssq[m * nblk + b];
+                    inv = 1.0f / sqrtf(t * inv_d + eps);
+                }
                 float act[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float gt = acc[0][mt][r], up = acc[1][mt][r];
+                    const float gt = acc[0][mt][r] * inv, up = acc[1][mt][r] * inv;
                     act[r] = gt / (1.0f + expf(-gt)) * up;
                 }
 #pragma unroll
@@ -350,13 +360,13 @@ GemmPlan gemm_plan_wide(int m_rows, int N, int K, int forced_split, int forced_n
 }
 
 void launch_gemm_wide(const u32x4* Wt, const float* wscale, const u32x4* Apk, float* P, int mt_total, int N, int K,
-                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out, LaunchStamps st) {
+                      GemmPlan plan, hipStream_t s, u32x4* swiglu_out, LaunchStamps st, const float* ssq, int nblk, float rms_eps) {
     const int n_tiles = N / 32, total_chunks = (K + 63) / 64, m_groups = (mt_total + plan.mt - 1) / plan.mt;
     const size_t split_stride = (size_t)mt_total * 32 * N;
     const int nt = plan.nt;
     const int tiles_x = (n_tiles + 4 * nt - 1) / (4 * nt);
     dim3 grid(std::min(tiles_x * m_groups, 256), 1, plan.split_k);
-#define WARGS Wt, wscale, Apk, P, split_stride, N, mt_total, n_tiles, total_chunks, plan.chunks_per_split, tiles_x, m_groups, swiglu_out
+#define WARGS Wt, wscale, Apk, P, split_stride, N, mt_total, n_tiles, total_chunks, plan.chunks_per_split, tiles_x, m_groups, swiglu_out, ssq, nblk, 1.0f / (float)K, rms_eps
 #define WLAUNCH(NT_, EPI_, ST_, MT_) hipExtLaunchKernelGGL(HIP_KERNEL_NAME(gemm_wide_kernel<NT_, EPI_, ST_, MT_>), grid, dim3(256), 0, s, st.start, st.stop, 0, WARGS)
     const bool stream = m_groups == 1;                  // (a single row group never takes the 192-row tile)
     if (plan.mt == 6) {

@@ -165,3 +165,45 @@ def test_wide_format_forward_agrees_with_two_bf16_terms():
     assert worst <= 5e-3
     for (Kw, Vw), (Kb, Vb) in zip(kvw, kvb):
         assert np.abs(Kw - Kb).max() <= 5e-4 * np.abs(Kb).max() and np.abs(Vw - Vb).max() <= 5e-4 * np.abs(Vb).max()
+
+
+def test_swiglu_in_the_gemm_epilogue_with_the_deferred_norm_scale():
+    """Block steps of at most 128 rows pack the FFN input without its RMSNorm scale; with very many FFN columns the
+    gate/up plan has two tiles per wave and k whole, and the wide-format kernel's epilogue then applies SiLU(gate) * up
+    itself, scaling both by 1 / rms.  With the wide format off the same forward goes through the two-term kernel and
+    the separate SwiGLU kernel: logits agree to well inside the parity tolerance, caches to a few 1e-4 of their scale."""
+    from paper_2605_29233_amd import BlockBatch, Limits, BB_INIT
+    from paper_2605_29233_amd.binding import gemm_plan
+    from workload.gen import gen_weights, gen_prompt
+    shape = ModelShape("fusetest", 2, 256, 4, 4, 64, 16640 + 16, 1024, qkv_bias=False)       # d_ffn % 64 != 0 as well
+    ngu = (shape.d_ffn + 63) // 64 * 128
+    p = gemm_plan(56, ngu, shape.d_model, wide=True)
+    assert p["nt"] == 2 and p["split_k"] == 1, p        # the case this test is here for
+    decode = DecodeParams(0.9, 0.5, 4, 8)
+    weights = dict(gen_weights(shape, 7))
+    prompt = gen_prompt(shape, 7, 0, 40)
+    G, blocks = 64, (8, 16, 32)
+    res = {}
+    for wide in (True, False):
+        b = BlockBatch(shape, decode, Limits(1, 3, 40 + G, G, 56), poison_workspace=True)
+        try:
+            b.load_weights(weights.items())
+            b.keep_logits(True)
+            b.wide_format(wide)
+            rid = b.request_open(prompt, G, blocks)
+            b.refresh([rid], BB_INIT)
+            b.merge_commit([rid])
+            outs = []
+            for step in range(3):
+                v = b.denoise_step([rid])
+                outs.append(v.logits().copy())
+                b.merge_commit([rid])
+            res[wide] = (outs, [b.get_kv(rid, k, l) for k in range(3) for l in range(2)])
+        finally:
+            b.close()
+    for a, r in zip(res[True][0], res[False][0]):
+        assert a.shape == r.shape and np.isfinite(a).all()
+        assert np.abs(a - r).max() <= 1e-2, np.abs(a - r).max()
+    for (K, V), (Kr, Vr) in zip(res[True][1], res[False][1]):
+        assert np.abs(K - Kr).max() <= 1e-3 * max(1.0, np.abs(Kr).max())
+        assert np.abs(V - Vr).max() <= 1e-3 * max(1.0, np.abs(Vr).max())
